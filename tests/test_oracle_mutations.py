@@ -1,0 +1,42 @@
+"""The pins must bite: each plausible mistake planted in a COPY of the oracle source
+(on the CPU, never in the GPU code) has to make at least one pin test fail."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "gac_oracle.cpp")
+
+# (name, text in the oracle source, replacement)
+MUTATIONS = [
+    ("eps_under_sqrt", "s_gd / (std::sqrt(s_gg * s_dd) + eps)", "s_gd / std::sqrt(s_gg * s_dd + eps)"),
+    ("dropped_eps", "s_gd / (std::sqrt(s_gg * s_dd) + eps)", "s_gd / std::sqrt(s_gg * s_dd)"),
+    ("safe_exclusive", "if (a <= c_low) {", "if (a < c_low) {"),
+    ("skip_exclusive", "} else if (a >= c_high) {", "} else if (a > c_high) {"),
+    ("signed_threshold", "const double a = std::fabs(c);", "const double a = c;"),
+    ("alpha_inverted", "out->alpha = c_low / a;", "out->alpha = a / c_low;"),
+    ("norm_of_g_for_u", "const double norm_d = std::sqrt(sums[2]);", "const double norm_d = std::sqrt(sums[1]);"),
+    ("rank_one_wrong_norm", "(alpha - beta) * (sums[0] / sums[2])", "(alpha - beta) * (sums[0] / sums[1])"),
+    ("rank_one_sign", "(alpha - beta) * (sums[0] / sums[2])", "(beta - alpha) * (sums[0] / sums[2])"),
+    ("perp_dropped", "g_out[i] = alpha * g_par + beta * g_perp;", "g_out[i] = alpha * g_par;"),
+    ("sums_swapped", "out[1] = s_gg;\n  out[2] = s_dd;", "out[1] = s_dd;\n  out[2] = s_gg;"),
+    ("state_not_updated_on_skip", "if (!dec.nonfinite) {", "if (!dec.nonfinite && dec.regime != ORACLE_SKIP) {"),
+    ("bf16_low_half", "static_cast<uint32_t>(h) << 16;", "static_cast<uint32_t>(h) << 15;"),
+    ("adam_no_bias_correction2", "std::sqrt(vi / bc2)", "std::sqrt(vi)"),
+    ("adam_coupled_decay", "pi = pi - lr * weight_decay * pi;", "pi = pi - weight_decay * pi;"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_planted_mistake_is_caught(tmp_path, name, old, new):
+    text = open(SRC).read()
+    assert text.count(old) == 1, f"mutation anchor for {name} not unique in the oracle source"
+    mutated = tmp_path / "gac_oracle_mutated.cpp"
+    mutated.write_text(text.replace(old, new))
+    env = dict(os.environ, GAC_ORACLE_SRC=str(mutated), GAC_ORACLE_LIB=str(tmp_path / "libmut.so"))
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
+                        os.path.join(ROOT, "tests", "test_oracle_pins.py")],
+                       cwd=ROOT, env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 1, f"mutation {name} survived the pins:\n{r.stdout[-2000:]}"

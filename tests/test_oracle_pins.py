@@ -1,0 +1,352 @@
+"""Pins for the CPU oracle: each test checks it against something fixed by the paper
+or by mathematics, never against the oracle's own arithmetic.
+
+Citations are to arXiv 2603.01501: Eq. 1 / Appendix A.1 (cosine with epsilon),
+Section 4.2 + Algorithm 1 (regimes), Eq. 2-4 (decomposition and rescale),
+Appendix A.2 (rank-one form, alpha = c_low/|c|, beta = 1), Proposition 4.1's proof
+(Pythagorean identity of the orthogonal projector; u = 0 when the reference is 0).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import gac_oracle as O
+from paper_2603_01501_amd import workloads as W
+from tests.golden_cases import load_cases
+
+C_LOW, C_HIGH, EPS = 0.05, 0.3, 1e-8
+REGIME = {"safe": O.SAFE, "project": O.PROJECT, "skip": O.SKIP}
+
+
+def f32(x):
+    return np.ascontiguousarray(np.asarray(x, dtype=np.float32))
+
+
+def bf16_bits(x):
+    """float -> bfloat16 bit patterns via torch's own conversion (a library routine)."""
+    t = torch.tensor(np.asarray(x, dtype=np.float32)).to(torch.bfloat16)
+    return t.view(torch.int16).numpy().view(np.uint16).copy()
+
+
+# ---------------------------------------------------------------- hand-worked cases
+
+@pytest.mark.parametrize("case", load_cases(), ids=lambda c: c["case"])
+@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
+def test_hand_worked_cases(case, dtype):
+    # All inputs are small integers, exactly representable in both storage dtypes.
+    conv = f32 if dtype == O.F32 else bf16_bits
+    g, d = conv(case["g"]), conv(case["d"])
+    s = O.sums([g], [d], dtype)
+    assert s.tolist() == case["sums"]
+    dec = O.decide(s, C_LOW, C_HIGH, case["eps"])
+    assert dec.regime == REGIME[case["regime"]]
+    assert dec.c == pytest.approx(case["c"], rel=0, abs=2e-16)
+    assert dec.alpha == pytest.approx(case["alpha"], rel=4e-16)
+    d_before = d.copy()
+    outs, s2, dec2 = O.step([g], [d], dtype, C_LOW, C_HIGH, case["eps"])
+    assert dec2.regime == dec.regime and s2.tolist() == s.tolist()
+    np.testing.assert_allclose(outs[0], case["gprime"], rtol=1e-15, atol=1e-16)
+    # state becomes the RAW gradient, bit for bit, in every regime
+    assert d.tobytes() == g.tobytes()
+    if dec.regime == O.PROJECT:
+        for fn in (O.project_decomposed, O.project_rank_one):
+            np.testing.assert_allclose(fn(g, d_before, dtype, s, dec.alpha), case["gprime"],
+                                       rtol=1e-15, atol=1e-16)
+
+
+def test_brute_force_python_loop_length8():
+    """Eq. 2-4 evaluated with plain Python floats and loops on random length-8 vectors."""
+    rng = np.random.default_rng(7)
+    for trial in range(50):
+        g = f32(rng.integers(-8, 9, size=8))
+        d = f32(rng.integers(-8, 9, size=8))
+        if not d.any() or not g.any():
+            continue
+        gd = sum(float(a) * float(b) for a, b in zip(g, d))
+        gg = sum(float(a) ** 2 for a in g)
+        dd = sum(float(b) ** 2 for b in d)
+        c = gd / (math.sqrt(gg * dd) + EPS)
+        s = O.sums([g], [d], O.F32)
+        assert s.tolist() == [gd, gg, dd]  # integers: exact
+        lo, hi = 0.2, 0.8
+        dec = O.decide(s, lo, hi, EPS)
+        assert dec.c == pytest.approx(c, abs=1e-16)
+        if abs(c) <= lo:
+            want_regime, want = O.SAFE, [float(a) for a in g]
+        elif abs(c) >= hi:
+            want_regime, want = O.SKIP, [float(a) for a in g]
+        else:
+            want_regime = O.PROJECT
+            alpha = lo / abs(c)
+            nd = math.sqrt(dd)
+            u = [float(b) / nd for b in d]
+            gu = sum(float(a) * ub for a, ub in zip(g, u))
+            want = [alpha * gu * ub + (float(a) - gu * ub) for a, ub in zip(g, u)]
+        outs, _, dec2 = O.step([g], [d.copy()], O.F32, lo, hi, EPS)
+        assert dec2.regime == want_regime
+        np.testing.assert_allclose(outs[0], want, rtol=1e-13, atol=1e-14)
+
+
+# ---------------------------------------------------------------- cosine closed forms
+
+def test_cos_of_vector_with_itself():
+    rng = np.random.default_rng(1)
+    g = f32(rng.standard_normal(1000))
+    s = O.sums([g], [g], O.F32)
+    assert s[0] == s[1] == s[2]
+    dec = O.decide(s, C_LOW, C_HIGH, EPS)
+    # c = |g|^2 / (|g|^2 + eps)  (Appendix A.1: eps outside the square root)
+    assert dec.c == pytest.approx(1.0 / (1.0 + EPS / s[1]), abs=1e-15)
+    assert dec.regime == O.SKIP
+    assert O.decide(s, C_LOW, C_HIGH, 0.0).c == 1.0
+
+
+def test_epsilon_sits_outside_the_square_root():
+    # tiny vectors make the two placements of eps differ by orders of magnitude
+    g, d = f32([1e-6, 0]), f32([1e-6, 0])
+    s = O.sums([g], [d], O.F32)
+    x = float(np.float32(1e-6)) ** 2
+    assert O.decide(s, C_LOW, C_HIGH, EPS).c == pytest.approx(x / (x + EPS), rel=1e-12)
+    assert O.decide(s, C_LOW, C_HIGH, EPS).c < 1e-3
+
+
+def test_orthogonal_and_zero_reference():
+    g = f32([1, 2, 3, 0, 0, 0])
+    d = f32([0, 0, 0, 4, 5, 6])
+    assert O.decide(O.sums([g], [d], O.F32), C_LOW, C_HIGH, EPS).c == 0.0
+    # first step: reference state is zero (Algorithm 1 initialisation) -> c = 0, safe
+    z = f32(np.zeros(6))
+    s = O.sums([g], [z], O.F32)
+    dec = O.decide(s, C_LOW, C_HIGH, EPS)
+    assert (dec.c, dec.regime, dec.alpha) == (0.0, O.SAFE, 1.0)
+    outs, _, _ = O.step([g], [z], O.F32, C_LOW, C_HIGH, EPS)
+    assert outs[0].tolist() == [1, 2, 3, 0, 0, 0] and z.tolist() == g.tolist()
+
+
+def test_scale_invariance_and_sign():
+    rng = np.random.default_rng(2)
+    d = f32(rng.standard_normal(4096))
+    g = f32(0.2 * d + rng.standard_normal(4096))
+    c0 = O.decide(O.sums([g], [d], O.F32), C_LOW, C_HIGH, 0.0).c
+    # power-of-two scalings are exact in floating point, so c is bit-identical
+    c1 = O.decide(O.sums([f32(g * 4)], [f32(d * 0.125)], O.F32), C_LOW, C_HIGH, 0.0).c
+    assert c1 == c0
+    c2 = O.decide(O.sums([f32(-g)], [d], O.F32), C_LOW, C_HIGH, 0.0).c
+    assert c2 == -c0
+
+
+@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
+def test_sums_against_numpy_dot(dtype):
+    rng = np.random.default_rng(3)
+    sizes = [1, 7, 1000, 4097, 33]
+    if dtype == O.F32:
+        gs = [f32(rng.standard_normal(n)) for n in sizes]
+        ds = [f32(rng.standard_normal(n)) for n in sizes]
+        g64 = np.concatenate(gs).astype(np.float64)
+        d64 = np.concatenate(ds).astype(np.float64)
+    else:
+        gs = [bf16_bits(rng.standard_normal(n)) for n in sizes]
+        ds = [bf16_bits(rng.standard_normal(n)) for n in sizes]
+        widen = lambda a: W.from_bits(a, torch.bfloat16).to(torch.float64).numpy()
+        g64 = np.concatenate([widen(a) for a in gs])
+        d64 = np.concatenate([widen(a) for a in ds])
+    s = O.sums(gs, ds, dtype)
+    want = [np.dot(g64, d64), np.dot(g64, g64), np.dot(d64, d64)]
+    np.testing.assert_allclose(s, want, rtol=1e-13)
+    # a list is the concatenation: the sequential sum is bit-identical to the flat one
+    flat = O.sums([np.concatenate(gs)], [np.concatenate(ds)], dtype)
+    assert flat.tolist() == s.tolist()
+
+
+def test_bf16_widening_bit_patterns():
+    # 0x3F80 = 1, 0xC000 = -2, 0x3DCD = 0.10009765625, 0x0001 = 2^-133 (subnormal), 0x8000 = -0
+    bits = np.array([0x3F80, 0xC000, 0x3DCD, 0x0001, 0x8000], dtype=np.uint16)
+    out = O.passthrough(bits, O.BF16)
+    assert out.tolist() == [1.0, -2.0, 0.10009765625, 2.0 ** -133, -0.0]
+    assert math.copysign(1.0, out[4]) == -1.0
+
+
+def test_sample_correlation_matches_population():
+    # g = rho d + sqrt(1-rho^2) z  =>  c within rho +- 5 (1-rho^2)/sqrt(N)
+    N = 1 << 18
+    for rho in (0.0, 0.5, 0.9):
+        g, d = W.correlated_pair([(N,)], torch.float32, rho, 1.0, config_id=1)
+        c = O.decide(O.sums([W.to_oracle_array(g[0])], [W.to_oracle_array(d[0])], O.F32),
+                     C_LOW, C_HIGH, EPS).c
+        assert abs(c - rho) <= 5 * (1 - rho * rho) / math.sqrt(N) + 1e-9
+
+
+# ---------------------------------------------------------------- regimes
+
+def test_regime_boundaries_are_inclusive():
+    # d = e1, g = (3,4): c = 3/5 exactly when eps = 0
+    g, d = f32([3, 4]), f32([1, 0])
+    s = O.sums([g], [d], O.F32)
+    assert O.decide(s, 0.1, 0.9, 0.0).c == 0.6
+    assert O.decide(s, 0.6, 0.9, 0.0).regime == O.SAFE      # |c| <= c_low
+    assert O.decide(s, 0.1, 0.6, 0.0).regime == O.SKIP      # |c| >= c_high
+    assert O.decide(s, math.nextafter(0.6, 0), 0.9, 0.0).regime == O.PROJECT
+    assert O.decide(s, 0.1, math.nextafter(0.6, 1), 0.0).regime == O.PROJECT
+    # negative alignment uses |c|
+    s_neg = O.sums([f32([-3, 4])], [d], O.F32)
+    assert O.decide(s_neg, 0.6, 0.9, 0.0).regime == O.SAFE
+    assert O.decide(s_neg, 0.1, 0.6, 0.0).regime == O.SKIP
+    dec = O.decide(s_neg, 0.1, 0.9, 0.0)
+    assert dec.regime == O.PROJECT and dec.alpha == pytest.approx(0.1 / 0.6, rel=1e-15)
+
+
+def test_safe_is_tested_before_violation():
+    # Algorithm 1 tests the safe branch first; with c_low >= |c| >= c_high impossible under
+    # 0 < c_low < c_high, the order only shows when |c| = c_low: still safe, alpha = 1.
+    s = np.array([3.0, 25.0, 1.0])
+    dec = O.decide(s, 0.6, 0.600000001, 0.0)
+    assert dec.regime == O.SAFE and dec.alpha == 1.0
+
+
+def test_nonfinite_convention():
+    dec = O.decide(np.array([float("nan"), 1.0, 1.0]), C_LOW, C_HIGH, EPS)
+    assert dec.nonfinite == 1 and dec.regime == O.SKIP
+    g, d = f32([float("inf"), 1]), f32([1, 1])
+    d0 = d.copy()
+    outs, _, dec = O.step([g], [d], O.F32, C_LOW, C_HIGH, EPS)
+    assert dec.nonfinite == 1 and d.tolist() == d0.tolist()
+
+
+# ---------------------------------------------------------------- projection invariants
+
+def _random_case(n=5000, rho=0.2, seed=11, dtype=O.F32):
+    rng = np.random.default_rng(seed)
+    d = rng.standard_normal(n)
+    g = rho * d + math.sqrt(1 - rho * rho) * rng.standard_normal(n)
+    conv = f32 if dtype == O.F32 else bf16_bits
+    return conv(g), conv(d)
+
+
+def _widen(a, dtype):
+    if dtype == O.F32:
+        return a.astype(np.float64)
+    return W.from_bits(a, torch.bfloat16).to(torch.float64).numpy()
+
+
+@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
+@pytest.mark.parametrize("rho", [0.2, -0.15])
+def test_projection_closed_forms(dtype, rho):
+    g, d = _random_case(rho=rho, dtype=dtype)
+    g64, d64 = _widen(g, dtype), _widen(d, dtype)
+    s = O.sums([g], [d], dtype)
+    dec = O.decide(s, C_LOW, C_HIGH, 0.0)
+    assert dec.regime == O.PROJECT
+    c, sign = dec.c, math.copysign(1.0, dec.c)
+    gp = O.project_decomposed(g, d, dtype, s, dec.alpha)
+    norm_g, norm_d = math.sqrt(np.dot(g64, g64)), math.sqrt(np.dot(d64, d64))
+    u = d64 / norm_d
+    # the component along u is brought to the target level:  <g',u> = sign(c) c_low |g|
+    assert np.dot(gp, u) == pytest.approx(sign * C_LOW * norm_g, rel=1e-12)
+    # |g'|^2 = |g|^2 (1 - c^2 + c_low^2)   (Pythagoras: alpha^2 <g,u>^2 + |g_perp|^2)
+    assert np.dot(gp, gp) == pytest.approx(norm_g ** 2 * (1 - c * c + C_LOW ** 2), rel=1e-12)
+    # cos(g', d) = sign(c) c_low / sqrt(1 - c^2 + c_low^2)
+    cos_after = np.dot(gp, d64) / (math.sqrt(np.dot(gp, gp)) * norm_d)
+    assert cos_after == pytest.approx(sign * C_LOW / math.sqrt(1 - c * c + C_LOW ** 2), rel=1e-12)
+    # only the component along d changes: g' - g is a multiple of d, and P_perp g' = P_perp g
+    k = (dec.alpha - 1.0) * s[0] / s[2]
+    np.testing.assert_allclose(gp - g64, k * d64, rtol=0, atol=1e-14 * norm_g)
+    perp = lambda x: x - np.dot(x, u) * u
+    np.testing.assert_allclose(perp(gp), perp(g64), rtol=0, atol=1e-13)
+    # the attenuation is an attenuation: 0 < alpha < 1 and the parallel part keeps its sign
+    assert 0 < dec.alpha < 1 and np.dot(gp, u) * np.dot(g64, u) > 0
+
+
+@pytest.mark.parametrize("beta", [1.0, 0.7])
+def test_rank_one_equals_decomposed(beta):
+    g, d = _random_case(n=3001, rho=0.25)
+    s = O.sums([g], [d], O.F32)
+    a = O.project_decomposed(g, d, O.F32, s, 0.3, beta)
+    b = O.project_rank_one(g, d, O.F32, s, 0.3, beta)
+    np.testing.assert_allclose(a, b, rtol=1e-13, atol=1e-15)
+    # alpha = beta = 1 is the identity; alpha = beta = b is a uniform scaling (Eq. 3)
+    np.testing.assert_allclose(O.project_decomposed(g, d, O.F32, s, 1.0, 1.0), g.astype(np.float64),
+                               rtol=1e-15, atol=1e-16)
+    np.testing.assert_allclose(O.project_rank_one(g, d, O.F32, s, 0.5, 0.5), 0.5 * g.astype(np.float64),
+                               rtol=1e-15)
+
+
+def test_projection_is_linear_in_g_for_fixed_reference():
+    g, d = _random_case(n=2048, rho=0.2)
+    outs1, _, dec1 = O.step([g], [d.copy()], O.F32, C_LOW, C_HIGH, 0.0)
+    outs2, _, dec2 = O.step([f32(g * 8)], [d.copy()], O.F32, C_LOW, C_HIGH, 0.0)
+    assert dec1.c == dec2.c and dec1.regime == O.PROJECT
+    np.testing.assert_allclose(outs2[0], 8 * outs1[0], rtol=1e-15)
+
+
+def test_global_statistic_over_the_list_not_per_tensor():
+    # two tensors: the first alone is orthogonal to its reference, the second alone is
+    # parallel; the cosine is one number over the concatenation
+    g = [f32([1, 0]), f32([2])]
+    d = [f32([0, 1]), f32([2])]
+    s = O.sums(g, d, O.F32)
+    assert s.tolist() == [4.0, 5.0, 5.0]
+    dec = O.decide(s, 0.1, 0.9, 0.0)
+    assert dec.c == pytest.approx(0.8, abs=1e-16) and dec.regime == O.PROJECT
+    outs, _, _ = O.step(g, [x.copy() for x in d], O.F32, 0.1, 0.9, 0.0)
+    # <g,u> u = (4/5) d;  g' = g + (alpha-1)(4/5) d,  alpha = 0.125
+    k = (0.125 - 1) * 0.8
+    np.testing.assert_allclose(outs[0], [1, k], rtol=1e-15)
+    np.testing.assert_allclose(outs[1], [2 + 2 * k], rtol=1e-15)
+
+
+def test_state_carries_raw_gradient_over_steps():
+    """Three consecutive steps: the reference of step t is the raw g of step t-1 even when
+    step t-1 was projected."""
+    rng = np.random.default_rng(5)
+    n = 4096
+    g1 = f32(rng.standard_normal(n))
+    g2 = f32(0.2 * g1 + rng.standard_normal(n))
+    g3 = f32(0.2 * g2 + rng.standard_normal(n))
+    d = f32(np.zeros(n))
+    _, _, dec1 = O.step([g1], [d], O.F32, C_LOW, C_HIGH, EPS)
+    assert dec1.regime == O.SAFE and d.tobytes() == g1.tobytes()
+    out2, s2, dec2 = O.step([g2], [d], O.F32, C_LOW, C_HIGH, EPS)
+    assert dec2.regime == O.PROJECT and d.tobytes() == g2.tobytes()
+    assert not np.array_equal(out2[0], g2.astype(np.float64))
+    _, s3, dec3 = O.step([g3], [d], O.F32, C_LOW, C_HIGH, EPS)
+    g2_64, g3_64 = g2.astype(np.float64), g3.astype(np.float64)
+    assert s3[0] == pytest.approx(np.dot(g3_64, g2_64), rel=1e-13)   # raw g2, not g2'
+    assert s3[2] == pytest.approx(np.dot(g2_64, g2_64), rel=1e-13)
+
+
+# ---------------------------------------------------------------- AdamW
+
+@pytest.mark.parametrize("t", [1, 2, 10])
+def test_adamw_against_torch_fp64(t):
+    rng = np.random.default_rng(9)
+    n = 513
+    p = f32(rng.standard_normal(n))
+    m = f32(rng.standard_normal(n) * 1e-3)
+    v = f32(np.abs(rng.standard_normal(n)) * 1e-6)
+    g = rng.standard_normal(n) * 1e-3
+    hp = dict(lr=1e-3, betas=(0.9, 0.999), eps=1e-8, weight_decay=1e-2)
+    po, mo, vo = O.adamw(g, p, m, v, hp["lr"], 0.9, 0.999, hp["eps"], hp["weight_decay"], t)
+    param = torch.nn.Parameter(torch.tensor(p, dtype=torch.float64))
+    opt = torch.optim.AdamW([param], **hp)
+    opt.state[param] = {"step": torch.tensor(float(t - 1)),
+                        "exp_avg": torch.tensor(m, dtype=torch.float64),
+                        "exp_avg_sq": torch.tensor(v, dtype=torch.float64)}
+    param.grad = torch.tensor(g, dtype=torch.float64)
+    opt.step()
+    np.testing.assert_allclose(po, param.detach().numpy(), rtol=1e-13, atol=1e-16)
+    np.testing.assert_allclose(mo, opt.state[param]["exp_avg"].numpy(), rtol=1e-13, atol=1e-18)
+    np.testing.assert_allclose(vo, opt.state[param]["exp_avg_sq"].numpy(), rtol=1e-13, atol=1e-20)
+
+
+def test_adamw_table2_hyperparameters_first_step_closed_form():
+    # t = 1, m = v = 0:  m_hat = g, v_hat = g^2  ->  p' = p (1 - lr wd) - lr g/(|g| + eps)
+    p, z = f32([1.0, -2.0]), f32([0, 0])
+    g = np.array([0.5, -0.25])
+    lr, wd, eps = 1e-6, 1e-2, 1e-8
+    po, mo, vo = O.adamw(g, p, z, z, lr, 0.9, 0.999, eps, wd, 1)
+    want = [pi * (1 - lr * wd) - lr * gi / (abs(gi) + eps) for pi, gi in zip([1.0, -2.0], g)]
+    np.testing.assert_allclose(po, want, rtol=1e-15)
+    np.testing.assert_allclose(mo, 0.1 * g, rtol=1e-15)
+    np.testing.assert_allclose(vo, 0.001 * g * g, rtol=1e-12)
