@@ -1,0 +1,186 @@
+/* gac.h - C ABI of the MI355X Gradient Alignment Control (GAC) step library.
+ *
+ * One call of gac_step() is one iteration of the body of Algorithm 1 of
+ * "GAC: Stabilizing Asynchronous RL Training for LLMs via Gradient Alignment
+ * Control" (arXiv 2603.01501) between "gradient is ready" and "optimizer
+ * consumes it":
+ *
+ *   1. three inner products <g,d>, <g,g>, <d,d> over the whole list of
+ *      parameter gradients g and the reference state d (Appendix A.1),
+ *   2. c = <g,d> / (sqrt(<g,g><d,d>) + eps)                  (Eq. 1, App. A.1),
+ *   3. regime: |c| <= c_low safe, |c| >= c_high violation (skip the update),
+ *      otherwise projection                           (Section 4.2, Algorithm 1),
+ *   4. projection: g <- beta g + (alpha - beta) <g,u> u in place, u = d/|d|,
+ *      alpha = c_low/|c|, beta = 1                   (Eq. 2-4, Appendix A.2),
+ *   5. d <- raw g of this step: the reference of the next step
+ *      (Algorithm 1 initialises it to zero; Appendix A.2 "gradient snapshot").
+ *
+ * General rules
+ *   - Every pointer named "device" is GPU memory owned by the caller (for
+ *     example PyTorch tensors); every other pointer is host memory.  Pointer
+ *     LISTS (grad_ptrs, state_ptrs, ...) are host arrays of device pointers,
+ *     one entry per tensor, copied during the call.
+ *   - Tensors are contiguous, element-aligned; 16-byte aligned tensors take the
+ *     fast path, others a slower element-wise path with identical results up to
+ *     summation order.  numel may be 0.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued on it.  A context is not thread-safe and its calls
+ *     must be issued in stream order.
+ *   - Functions return GAC_OK (0) or a negative GAC_ERR_* code; nothing throws
+ *     or aborts across this boundary.  gac_strerror() names a code.
+ *   - Results are deterministic: the same inputs, configuration and device give
+ *     bit-identical sums, cosine and outputs on every call.
+ */
+#ifndef GAC_H_
+#define GAC_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gac_ctx gac_ctx; /* opaque */
+
+/* storage dtype of gradients and of the reference state */
+enum { GAC_F32 = 0, GAC_BF16 = 1 };
+
+/* regimes of Section 4.2 */
+enum { GAC_SAFE = 0, GAC_PROJECT = 1, GAC_SKIP = 2 };
+
+enum {
+  GAC_OK = 0,
+  GAC_ERR_INVALID_ARG = -1,    /* NULL where not allowed, negative sizes, bad dtype */
+  GAC_ERR_BAD_THRESHOLDS = -2, /* violates 0 < c_low < c_high, eps < 0, beta < 0 */
+  GAC_ERR_ALLOC = -3,          /* host or device allocation failed */
+  GAC_ERR_HIP = -4,            /* a HIP runtime call failed; see gac_last_hip_error() */
+  GAC_ERR_NONFINITE = -5,      /* a sum was inf/nan: nothing was modified (see gac_step) */
+  GAC_ERR_UNIMPLEMENTED = -6
+};
+
+typedef struct gac_config {
+  double c_low;   /* Section 4.2; paper default 0.05 (Appendix C, "GAC thresholds") */
+  double c_high;  /* paper default 0.3; values > 1 mean "never skip" */
+  double eps;     /* added to the cosine denominator, Appendix A.1; default 1e-8 */
+  double beta;    /* gain of the orthogonal part, Eq. 3; the paper uses 1 (Appendix A.2) */
+  int32_t dtype;  /* GAC_F32 or GAC_BF16 */
+  int32_t n_tensors;
+  const int64_t* numel;    /* host, n_tensors entries, copied by gac_init */
+  void* const* state_ptrs; /* host list of device buffers for d, one per tensor, each
+                              numel[j] elements of dtype, or NULL: the library allocates
+                              (and frees in gac_destroy) one buffer for all of d */
+  int32_t device;          /* HIP device ordinal; -1 = current device */
+  uint32_t flags;          /* must be 0 */
+  int32_t chunk_elems;     /* tuning: elements per work item of a block; 0 = default.
+                              Must be a positive multiple of 2048. */
+  int32_t grid_blocks;     /* tuning: workgroups per launch; 0 = default (8 per CU) */
+} gac_config;
+
+typedef struct gac_result {
+  double dot;  /* <g,d> */
+  double gg;   /* <g,g> */
+  double dd;   /* <d,d> */
+  double c;    /* cosine with eps; NaN if nonfinite */
+  double alpha;/* c_low/|c| in the projection regime, else 1 */
+  double coef; /* k in g' = beta g + k d;  (alpha-beta) <g,d>/<d,d> in the projection regime, else 0 */
+  int32_t regime;    /* GAC_SAFE / GAC_PROJECT / GAC_SKIP */
+  int32_t nonfinite; /* 1 if any sum was not finite */
+  int64_t step;      /* 1 for the first update after init/reset */
+} gac_result;
+
+/* AdamW hyper-parameters; the paper's values are lr 1e-6, betas (0.9, 0.999),
+ * eps 1e-8, weight decay 1e-2 (Table 2).  t_adam is the 1-based count of optimizer
+ * steps actually taken, owned by the caller (a skipped update does not count). */
+typedef struct gac_adamw_hyper {
+  double lr, beta1, beta2, eps_adam, weight_decay;
+  int64_t t_adam;
+} gac_adamw_hyper;
+
+/* Fills cfg with the paper's defaults (c_low 0.05, c_high 0.3, eps 1e-8, beta 1),
+ * dtype GAC_BF16, no tensors, device -1. */
+void gac_default_config(gac_config* cfg);
+
+/* Algorithm 1, initialisation: creates a context for a fixed list of tensor sizes and
+ * sets the reference state to zero (so the first step has c = 0 and is safe).
+ * Thresholds are validated first (0 < c_low < c_high, eps >= 0, beta >= 0), before any
+ * GPU call.  On failure *out is NULL. */
+int gac_init(gac_ctx** out, const gac_config* cfg);
+
+/* Frees everything the library allocated (never caller-provided state). NULL is allowed. */
+void gac_destroy(gac_ctx* ctx);
+
+/* One whole update (steps 1-5 above) on one GPU.
+ *   grad_ptrs  host list of n_tensors device pointers to g (modified in place only in the
+ *              projection regime).  May differ from call to call; sizes may not.
+ *   host_out   NULL: fully asynchronous.  Otherwise the call waits for the stream and
+ *              fills *host_out; the caller skips its optimizer step if regime is GAC_SKIP.
+ * The state d becomes the raw g in all three regimes.  If a sum is not finite (a
+ * convention of this library, the paper does not cover it): nonfinite = 1, regime =
+ * GAC_SKIP, neither g nor d is touched, and the return value is GAC_ERR_NONFINITE when
+ * host_out was given (otherwise GAC_OK, and the flag is in the device result). */
+int gac_step(gac_ctx* ctx, void* const* grad_ptrs, void* hip_stream, gac_result* host_out);
+
+/* Data-parallel form of the same update (Appendix A.1: each rank reduces its shard, one
+ * all-reduce of three scalars, then each rank applies).  Phase 1 writes the rank-local
+ * {<g,d>, <g,g>, <d,d>} to dev_sums3 (device, 3 doubles).  The caller sums them across
+ * ranks (in a fixed order, if bit-reproducibility across runs is wanted). */
+int gac_reduce_local(gac_ctx* ctx, void* const* grad_ptrs, void* hip_stream, double* dev_sums3);
+
+/* Phase 2: takes the GLOBAL sums (device, 3 doubles), decides the regime and applies
+ * steps 3-5 to the local shard.  gac_reduce_local + gac_apply on one rank with the same
+ * sums is exactly gac_step. */
+int gac_apply(gac_ctx* ctx, void* const* grad_ptrs, const double* dev_sums3, void* hip_stream,
+              gac_result* host_out);
+
+/* gac_step with the optimizer fused into the second pass: the projected gradient g' is
+ * formed in registers and consumed by AdamW (decoupled weight decay; Table 2 names the
+ * optimizer and its hyper-parameters) without being written back; g is left untouched.
+ *   m <- b1 m + (1-b1) g';  v <- b2 v + (1-b2) g'^2;  p <- p - lr wd p;
+ *   p <- p - lr (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps_adam)
+ * master_p, m, v: host lists of device fp32 buffers (numel[j] each), updated in place.
+ * p_lowp: optional host list of device buffers of the gradient dtype that receive the
+ * rounded new parameters (NULL = none).  In the GAC_SKIP regime (and on nonfinite) the
+ * optimizer state and parameters are not touched at all; d is still updated on SKIP. */
+int gac_step_adamw(gac_ctx* ctx, void* const* grad_ptrs, float* const* master_p, float* const* m,
+                   float* const* v, void* const* p_lowp, const gac_adamw_hyper* hyper,
+                   void* hip_stream, gac_result* host_out);
+
+/* Device address of the result of the most recent step, for callers that branch on the
+ * GPU.  Valid until gac_destroy; overwritten by the next step. */
+int gac_result_device(const gac_ctx* ctx, const gac_result** dev_ptr);
+
+/* Copies the reference state d to / from caller buffers (host lists of device pointers,
+ * numel[j] elements each).  Import also sets the step counter (checkpoint / resume). */
+int gac_state_export(gac_ctx* ctx, void* const* dst_ptrs, int64_t* step_out, void* hip_stream);
+int gac_state_import(gac_ctx* ctx, void* const* src_ptrs, int64_t step, void* hip_stream);
+
+/* d <- 0 and step <- 0: back to the state right after gac_init. */
+int gac_reset(gac_ctx* ctx, void* hip_stream);
+
+/* Replaces the thresholds (validated as in gac_init) for the following steps. */
+int gac_set_thresholds(gac_ctx* ctx, double c_low, double c_high);
+
+/* Host-only planning query (no GPU call): the number of work items the tensor list is cut
+ * into (no item straddles two tensors) and the total element count.  chunk_elems = 0 uses
+ * the default for the dtype. */
+int gac_plan_query(const int64_t* numel, int32_t n_tensors, int32_t dtype, int32_t chunk_elems,
+                   int64_t* n_chunks_out, int64_t* total_numel_out);
+
+/* Kernel timing for benchmarks.  While enabled, each step records HIP events on its stream
+ * around the reduction, the finalize and the apply kernels.  gac_profile_read waits for the
+ * recorded events and returns the summed milliseconds per kernel and the number of steps
+ * since the last read (which it then clears).  At most 1024 steps are kept. */
+int gac_profile_enable(gac_ctx* ctx, int32_t on);
+int gac_profile_read(gac_ctx* ctx, double* ms_reduce, double* ms_finalize, double* ms_apply,
+                     int32_t* n_steps);
+
+const char* gac_strerror(int code);
+/* Text of the last HIP error seen by this context (empty string if none).  With ctx = NULL:
+ * the last HIP error of any context on the calling thread (for a failed gac_init). */
+const char* gac_last_hip_error(const gac_ctx* ctx);
+const char* gac_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GAC_H_ */

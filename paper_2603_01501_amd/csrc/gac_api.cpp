@@ -1,0 +1,604 @@
+// Host side of the GAC step library: context, planner, pointer-table upload, C ABI.
+// Interface and semantics: include/gac.h.  Kernels: gac_kernels.hip.
+
+#include <hip/hip_runtime_api.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "gac_internal.h"
+
+using gac::AdamScalars;
+using gac::AdamSeg;
+using gac::DecideParams;
+using gac::Seg;
+
+namespace {
+
+constexpr int kPinnedSlots = 4;         // ring of pinned staging tables for pointer uploads
+constexpr int kDefaultChunkBytes = 65536;
+constexpr int kChunkMultiple = 2048;    // chunk_elems granularity (256 threads x 8 elements)
+constexpr int kDefaultBlocksPerCU = 8;
+constexpr int kMaxProfiledSteps = 1024;
+
+int64_t elem_size(int dtype) { return dtype == GAC_BF16 ? 2 : 4; }
+
+int default_chunk_elems(int dtype) { return kDefaultChunkBytes / static_cast<int>(elem_size(dtype)); }
+
+bool thresholds_ok(double c_low, double c_high) {
+  // Section 4.2: 0 < c_low < c_high.  (NaN fails every comparison.)
+  return c_low > 0.0 && c_high > c_low && std::isfinite(c_low) && !std::isnan(c_high);
+}
+
+// Cuts the tensor list into chunks.  first_chunk gets n_tensors + 1 entries.
+int plan(const int64_t* numel, int32_t n_tensors, int chunk_elems, std::vector<int64_t>* first_chunk,
+         int64_t* total) {
+  first_chunk->assign(static_cast<size_t>(n_tensors) + 1, 0);
+  int64_t c = 0, n = 0;
+  for (int32_t j = 0; j < n_tensors; ++j) {
+    if (numel[j] < 0) return GAC_ERR_INVALID_ARG;
+    (*first_chunk)[j] = c;
+    c += (numel[j] + chunk_elems - 1) / chunk_elems;
+    n += numel[j];
+  }
+  (*first_chunk)[n_tensors] = c;
+  *total = n;
+  return GAC_OK;
+}
+
+int resolve_chunk_elems(int dtype, int chunk_elems, int* out) {
+  if (dtype != GAC_F32 && dtype != GAC_BF16) return GAC_ERR_INVALID_ARG;
+  if (chunk_elems == 0) chunk_elems = default_chunk_elems(dtype);
+  if (chunk_elems < 0 || chunk_elems % kChunkMultiple != 0) return GAC_ERR_INVALID_ARG;
+  *out = chunk_elems;
+  return GAC_OK;
+}
+
+struct StepEvents {
+  hipEvent_t e[4];  // before reduce, after reduce, after finalize, after apply
+};
+
+}  // namespace
+
+struct gac_ctx {
+  int device = 0;
+  int dtype = GAC_BF16;
+  int n_tensors = 0;
+  std::vector<int64_t> numel;
+  std::vector<int64_t> first_chunk;
+  int64_t n_chunks = 0;
+  int64_t total = 0;
+  int chunk_elems = 0;
+  int grid = 1;
+  double c_low = 0, c_high = 0, eps = 0, beta = 1;
+  int64_t step = 0;
+
+  std::vector<void*> state;    // device pointers of d, one per tensor
+  void* state_alloc = nullptr; // owned allocation backing `state`, or null
+
+  // pointer tables
+  Seg* dev_segs = nullptr;
+  AdamSeg* dev_adam = nullptr;
+  Seg* pinned_segs[kPinnedSlots] = {};
+  AdamSeg* pinned_adam[kPinnedSlots] = {};
+  hipEvent_t slot_event[kPinnedSlots] = {};
+  int slot = 0;
+  std::vector<const void*> cached_a;  // what dev_segs currently holds in Seg::a
+  std::vector<void*> cached_b;        // ... and in Seg::b
+  bool segs_valid = false;
+  std::vector<AdamSeg> cached_adam;
+  bool adam_valid = false;
+
+  double* dev_partials = nullptr;  // 3 doubles per workgroup
+  double* dev_sums = nullptr;      // 3 doubles
+  gac_result* dev_result = nullptr;
+  gac_result* pinned_result = nullptr;
+  hipEvent_t result_event = nullptr;
+
+  bool profiling = false;
+  std::vector<StepEvents> prof_pool;
+  size_t prof_used = 0;
+
+  std::string hip_err;
+};
+
+namespace {
+
+struct DeviceGuard {
+  int prev = -1;
+  bool changed = false;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) == hipSuccess && prev != dev) changed = hipSetDevice(dev) == hipSuccess;
+  }
+  ~DeviceGuard() {
+    if (changed) (void)hipSetDevice(prev);
+  }
+};
+
+// Text of the last HIP failure of any context on this thread; survives a failed gac_init,
+// whose context is gone by the time the caller can ask.
+thread_local std::string g_last_hip_error;
+
+int fail_hip(gac_ctx* ctx, hipError_t e, const char* what) {
+  g_last_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+  if (ctx != nullptr) ctx->hip_err = g_last_hip_error;
+  return GAC_ERR_HIP;
+}
+
+#define GAC_HIP(ctx, call)                                  \
+  do {                                                      \
+    hipError_t e_ = (call);                                 \
+    if (e_ != hipSuccess) return fail_hip(ctx, e_, #call);  \
+  } while (0)
+
+// Makes dev_segs hold (a[j], b[j]) for every tensor.  Uploads only when something changed.
+int upload_segs(gac_ctx* ctx, const void* const* a, void* const* b, hipStream_t stream) {
+  const int n = ctx->n_tensors;
+  bool same = ctx->segs_valid;
+  for (int j = 0; same && j < n; ++j) same = ctx->cached_a[j] == (a ? a[j] : nullptr) && ctx->cached_b[j] == b[j];
+  if (same) return GAC_OK;
+  const int s = ctx->slot;
+  ctx->slot = (s + 1) % kPinnedSlots;
+  GAC_HIP(ctx, hipEventSynchronize(ctx->slot_event[s]));  // the slot's previous upload is done
+  Seg* host = ctx->pinned_segs[s];
+  for (int j = 0; j < n; ++j) {
+    host[j].a = a ? a[j] : nullptr;
+    host[j].b = b[j];
+    host[j].numel = ctx->numel[j];
+    host[j].first_chunk = ctx->first_chunk[j];
+    ctx->cached_a[j] = host[j].a;
+    ctx->cached_b[j] = host[j].b;
+  }
+  host[n].a = nullptr;
+  host[n].b = nullptr;
+  host[n].numel = 0;
+  host[n].first_chunk = ctx->n_chunks;
+  ctx->segs_valid = false;
+  GAC_HIP(ctx, hipMemcpyAsync(ctx->dev_segs, host, sizeof(Seg) * (n + 1), hipMemcpyHostToDevice, stream));
+  GAC_HIP(ctx, hipEventRecord(ctx->slot_event[s], stream));
+  ctx->segs_valid = true;
+  return GAC_OK;
+}
+
+int upload_adam(gac_ctx* ctx, float* const* p, float* const* m, float* const* v, void* const* pl,
+                hipStream_t stream) {
+  const int n = ctx->n_tensors;
+  bool same = ctx->adam_valid;
+  for (int j = 0; same && j < n; ++j) {
+    const AdamSeg& c = ctx->cached_adam[j];
+    same = c.p == p[j] && c.m == m[j] && c.v == v[j] && c.p_lowp == (pl ? pl[j] : nullptr);
+  }
+  if (same) return GAC_OK;
+  const int s = ctx->slot;
+  ctx->slot = (s + 1) % kPinnedSlots;
+  GAC_HIP(ctx, hipEventSynchronize(ctx->slot_event[s]));
+  AdamSeg* host = ctx->pinned_adam[s];
+  for (int j = 0; j < n; ++j) {
+    host[j].p = p[j];
+    host[j].m = m[j];
+    host[j].v = v[j];
+    host[j].p_lowp = pl ? pl[j] : nullptr;
+    ctx->cached_adam[j] = host[j];
+  }
+  ctx->adam_valid = false;
+  GAC_HIP(ctx, hipMemcpyAsync(ctx->dev_adam, host, sizeof(AdamSeg) * n, hipMemcpyHostToDevice, stream));
+  GAC_HIP(ctx, hipEventRecord(ctx->slot_event[s], stream));
+  ctx->adam_valid = true;
+  return GAC_OK;
+}
+
+int check_ptrs(const gac_ctx* ctx, const void* const* ptrs) {
+  if (ptrs == nullptr && ctx->n_tensors > 0) return GAC_ERR_INVALID_ARG;
+  for (int j = 0; j < ctx->n_tensors; ++j) {
+    if (ctx->numel[j] > 0 && ptrs[j] == nullptr) return GAC_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(ptrs[j]) % static_cast<uintptr_t>(elem_size(ctx->dtype)) != 0)
+      return GAC_ERR_INVALID_ARG;
+  }
+  return GAC_OK;
+}
+
+StepEvents* next_events(gac_ctx* ctx) {
+  if (!ctx->profiling || ctx->prof_used >= static_cast<size_t>(kMaxProfiledSteps)) return nullptr;
+  if (ctx->prof_used == ctx->prof_pool.size()) {
+    StepEvents ev;
+    for (auto& e : ev.e)
+      if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    ctx->prof_pool.push_back(ev);
+  }
+  return &ctx->prof_pool[ctx->prof_used++];
+}
+
+// Copies the device result to the host and waits for it.  The copy is ordered after the
+// finalize kernel only, so the host learns the regime while the apply kernel still runs.
+int fetch_result(gac_ctx* ctx, hipStream_t stream) {
+  GAC_HIP(ctx, hipMemcpyAsync(ctx->pinned_result, ctx->dev_result, sizeof(gac_result),
+                              hipMemcpyDeviceToHost, stream));
+  GAC_HIP(ctx, hipEventRecord(ctx->result_event, stream));
+  return GAC_OK;
+}
+
+int wait_result(gac_ctx* ctx, gac_result* host_out) {
+  GAC_HIP(ctx, hipEventSynchronize(ctx->result_event));
+  *host_out = *ctx->pinned_result;
+  return host_out->nonfinite ? GAC_ERR_NONFINITE : GAC_OK;
+}
+
+DecideParams decide_params(const gac_ctx* ctx) {
+  DecideParams p;
+  p.c_low = ctx->c_low;
+  p.c_high = ctx->c_high;
+  p.eps = ctx->eps;
+  p.beta = ctx->beta;
+  p.step = ctx->step;
+  return p;
+}
+
+int state_op(gac_ctx* ctx, int op, const void* const* src, void* const* dst, hipStream_t stream) {
+  int rc = upload_segs(ctx, src, dst, stream);
+  if (rc != GAC_OK) return rc;
+  GAC_HIP(ctx, gac::launch_state_op(ctx->dtype, op, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
+                                    ctx->grid, stream));
+  return GAC_OK;
+}
+
+// Steps shared by gac_step / gac_apply / gac_step_adamw after the sums are available.
+enum class ApplyKind { kPlain, kAdamW };
+
+int run_step(gac_ctx* ctx, void* const* grad_ptrs, bool do_reduce, const double* sums_in,
+             ApplyKind kind, const AdamScalars* adam, hipStream_t stream, gac_result* host_out) {
+  int rc = upload_segs(ctx, const_cast<const void* const*>(grad_ptrs), ctx->state.data(), stream);
+  if (rc != GAC_OK) return rc;
+  ctx->step += 1;
+  StepEvents* ev = next_events(ctx);
+  if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[0], stream));
+  int mode = 2;
+  if (do_reduce) {
+    GAC_HIP(ctx, gac::launch_reduce(ctx->dtype, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
+                                    ctx->dev_partials, ctx->grid, stream));
+    mode |= 1;
+  }
+  if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[1], stream));
+  GAC_HIP(ctx, gac::launch_finalize(ctx->dev_partials, ctx->grid, sums_in, ctx->dev_sums,
+                                    ctx->dev_result, decide_params(ctx), mode, stream));
+  if (host_out != nullptr) {
+    rc = fetch_result(ctx, stream);
+    if (rc != GAC_OK) return rc;
+  }
+  if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[2], stream));
+  const float beta = static_cast<float>(ctx->beta);
+  if (kind == ApplyKind::kPlain) {
+    GAC_HIP(ctx, gac::launch_apply(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
+                                   ctx->chunk_elems, ctx->dev_result, beta, ctx->grid, stream));
+  } else {
+    GAC_HIP(ctx, gac::launch_apply_adamw(ctx->dtype, ctx->dev_segs, ctx->dev_adam, ctx->n_tensors,
+                                         ctx->n_chunks, ctx->chunk_elems, ctx->dev_result, beta,
+                                         *adam, ctx->grid, stream));
+  }
+  if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[3], stream));
+  if (host_out != nullptr) return wait_result(ctx, host_out);
+  return GAC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+void gac_default_config(gac_config* cfg) {
+  if (cfg == nullptr) return;
+  std::memset(cfg, 0, sizeof(*cfg));
+  cfg->c_low = 0.05;
+  cfg->c_high = 0.3;
+  cfg->eps = 1e-8;
+  cfg->beta = 1.0;
+  cfg->dtype = GAC_BF16;
+  cfg->device = -1;
+}
+
+int gac_plan_query(const int64_t* numel, int32_t n_tensors, int32_t dtype, int32_t chunk_elems,
+                   int64_t* n_chunks_out, int64_t* total_numel_out) {
+  if (n_tensors < 0 || (n_tensors > 0 && numel == nullptr)) return GAC_ERR_INVALID_ARG;
+  int ce = 0;
+  int rc = resolve_chunk_elems(dtype, chunk_elems, &ce);
+  if (rc != GAC_OK) return rc;
+  std::vector<int64_t> fc;
+  int64_t total = 0;
+  rc = plan(numel, n_tensors, ce, &fc, &total);
+  if (rc != GAC_OK) return rc;
+  if (n_chunks_out) *n_chunks_out = fc[n_tensors];
+  if (total_numel_out) *total_numel_out = total;
+  return GAC_OK;
+}
+
+int gac_init(gac_ctx** out, const gac_config* cfg) {
+  if (out == nullptr) return GAC_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (cfg == nullptr || cfg->n_tensors < 0 || (cfg->n_tensors > 0 && cfg->numel == nullptr) ||
+      cfg->flags != 0 || cfg->grid_blocks < 0 || cfg->grid_blocks > gac::kMaxGridBlocks)
+    return GAC_ERR_INVALID_ARG;
+  if (!thresholds_ok(cfg->c_low, cfg->c_high) || !(cfg->eps >= 0.0) || !(cfg->beta >= 0.0) ||
+      !std::isfinite(cfg->eps) || !std::isfinite(cfg->beta))
+    return GAC_ERR_BAD_THRESHOLDS;
+  int chunk_elems = 0;
+  int rc = resolve_chunk_elems(cfg->dtype, cfg->chunk_elems, &chunk_elems);
+  if (rc != GAC_OK) return rc;
+
+  gac_ctx* ctx = new (std::nothrow) gac_ctx();
+  if (ctx == nullptr) return GAC_ERR_ALLOC;
+  struct Cleanup {
+    gac_ctx* c;
+    ~Cleanup() { if (c) gac_destroy(c); }
+  } cleanup{ctx};
+
+  ctx->dtype = cfg->dtype;
+  ctx->n_tensors = cfg->n_tensors;
+  ctx->chunk_elems = chunk_elems;
+  ctx->c_low = cfg->c_low;
+  ctx->c_high = cfg->c_high;
+  ctx->eps = cfg->eps;
+  ctx->beta = cfg->beta;
+  const int n = cfg->n_tensors;
+  ctx->numel.assign(cfg->numel, cfg->numel + n);
+  rc = plan(ctx->numel.data(), n, chunk_elems, &ctx->first_chunk, &ctx->total);
+  if (rc != GAC_OK) return rc;
+  ctx->n_chunks = ctx->first_chunk[n];
+  if (cfg->state_ptrs != nullptr) {
+    for (int j = 0; j < n; ++j)
+      if (ctx->numel[j] > 0 && cfg->state_ptrs[j] == nullptr) return GAC_ERR_INVALID_ARG;
+  }
+
+  // ---- from here on the GPU is touched
+  int dev = cfg->device;
+  if (dev < 0) GAC_HIP(ctx, hipGetDevice(&dev));
+  ctx->device = dev;
+  DeviceGuard guard(dev);
+  hipDeviceProp_t prop;
+  GAC_HIP(ctx, hipGetDeviceProperties(&prop, dev));
+  int64_t grid = cfg->grid_blocks > 0 ? cfg->grid_blocks
+                                      : static_cast<int64_t>(prop.multiProcessorCount) * kDefaultBlocksPerCU;
+  if (grid > ctx->n_chunks) grid = ctx->n_chunks;
+  if (grid < 1) grid = 1;
+  if (grid > gac::kMaxGridBlocks) grid = gac::kMaxGridBlocks;
+  ctx->grid = static_cast<int>(grid);
+
+  ctx->state.assign(n, nullptr);
+  if (cfg->state_ptrs != nullptr) {
+    for (int j = 0; j < n; ++j) ctx->state[j] = cfg->state_ptrs[j];
+  } else {
+    // one allocation, every tensor's slice 256-byte aligned
+    const int64_t es = elem_size(ctx->dtype);
+    int64_t bytes = 0;
+    std::vector<int64_t> off(n);
+    for (int j = 0; j < n; ++j) {
+      off[j] = bytes;
+      bytes += (ctx->numel[j] * es + 255) / 256 * 256;
+    }
+    if (bytes > 0) {
+      if (hipMalloc(&ctx->state_alloc, static_cast<size_t>(bytes)) != hipSuccess) {
+        (void)hipGetLastError();
+        return GAC_ERR_ALLOC;
+      }
+    }
+    for (int j = 0; j < n; ++j) ctx->state[j] = static_cast<char*>(ctx->state_alloc) + off[j];
+  }
+  rc = check_ptrs(ctx, const_cast<const void* const*>(ctx->state.data()));
+  if (rc != GAC_OK) return rc;
+
+  GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_segs), sizeof(Seg) * (n + 1)));
+  GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_adam), sizeof(AdamSeg) * (n > 0 ? n : 1)));
+  for (int s = 0; s < kPinnedSlots; ++s) {
+    GAC_HIP(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned_segs[s]), sizeof(Seg) * (n + 1), hipHostMallocDefault));
+    GAC_HIP(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned_adam[s]), sizeof(AdamSeg) * (n > 0 ? n : 1), hipHostMallocDefault));
+    GAC_HIP(ctx, hipEventCreateWithFlags(&ctx->slot_event[s], hipEventDisableTiming));
+  }
+  ctx->cached_a.assign(n, nullptr);
+  ctx->cached_b.assign(n, nullptr);
+  ctx->cached_adam.assign(n, AdamSeg{nullptr, nullptr, nullptr, nullptr});
+  GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_partials), sizeof(double) * 3 * ctx->grid));
+  GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_sums), sizeof(double) * 3));
+  GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_result), sizeof(gac_result)));
+  GAC_HIP(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned_result), sizeof(gac_result), hipHostMallocDefault));
+  GAC_HIP(ctx, hipEventCreateWithFlags(&ctx->result_event, hipEventDisableTiming));
+  std::memset(ctx->pinned_result, 0, sizeof(gac_result));
+
+  // Algorithm 1: the reference state starts at zero.
+  rc = state_op(ctx, gac::kStateZero, nullptr, ctx->state.data(), nullptr);
+  if (rc != GAC_OK) return rc;
+  GAC_HIP(ctx, hipStreamSynchronize(nullptr));
+
+  cleanup.c = nullptr;
+  *out = ctx;
+  return GAC_OK;
+}
+
+void gac_destroy(gac_ctx* ctx) {
+  if (ctx == nullptr) return;
+  {
+    DeviceGuard guard(ctx->device);
+    (void)hipDeviceSynchronize();
+    if (ctx->state_alloc) (void)hipFree(ctx->state_alloc);
+    if (ctx->dev_segs) (void)hipFree(ctx->dev_segs);
+    if (ctx->dev_adam) (void)hipFree(ctx->dev_adam);
+    if (ctx->dev_partials) (void)hipFree(ctx->dev_partials);
+    if (ctx->dev_sums) (void)hipFree(ctx->dev_sums);
+    if (ctx->dev_result) (void)hipFree(ctx->dev_result);
+    if (ctx->pinned_result) (void)hipHostFree(ctx->pinned_result);
+    if (ctx->result_event) (void)hipEventDestroy(ctx->result_event);
+    for (int s = 0; s < kPinnedSlots; ++s) {
+      if (ctx->pinned_segs[s]) (void)hipHostFree(ctx->pinned_segs[s]);
+      if (ctx->pinned_adam[s]) (void)hipHostFree(ctx->pinned_adam[s]);
+      if (ctx->slot_event[s]) (void)hipEventDestroy(ctx->slot_event[s]);
+    }
+    for (auto& ev : ctx->prof_pool)
+      for (auto& e : ev.e) (void)hipEventDestroy(e);
+  }
+  delete ctx;
+}
+
+int gac_step(gac_ctx* ctx, void* const* grad_ptrs, void* hip_stream, gac_result* host_out) {
+  if (ctx == nullptr) return GAC_ERR_INVALID_ARG;
+  int rc = check_ptrs(ctx, const_cast<const void* const*>(grad_ptrs));
+  if (rc != GAC_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  return run_step(ctx, grad_ptrs, true, nullptr, ApplyKind::kPlain, nullptr,
+                  static_cast<hipStream_t>(hip_stream), host_out);
+}
+
+int gac_reduce_local(gac_ctx* ctx, void* const* grad_ptrs, void* hip_stream, double* dev_sums3) {
+  if (ctx == nullptr || dev_sums3 == nullptr) return GAC_ERR_INVALID_ARG;
+  int rc = check_ptrs(ctx, const_cast<const void* const*>(grad_ptrs));
+  if (rc != GAC_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  rc = upload_segs(ctx, const_cast<const void* const*>(grad_ptrs), ctx->state.data(), stream);
+  if (rc != GAC_OK) return rc;
+  GAC_HIP(ctx, gac::launch_reduce(ctx->dtype, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
+                                  ctx->dev_partials, ctx->grid, stream));
+  GAC_HIP(ctx, gac::launch_finalize(ctx->dev_partials, ctx->grid, nullptr, dev_sums3, ctx->dev_result,
+                                    decide_params(ctx), /*mode=*/1, stream));
+  return GAC_OK;
+}
+
+int gac_apply(gac_ctx* ctx, void* const* grad_ptrs, const double* dev_sums3, void* hip_stream,
+              gac_result* host_out) {
+  if (ctx == nullptr || dev_sums3 == nullptr) return GAC_ERR_INVALID_ARG;
+  int rc = check_ptrs(ctx, const_cast<const void* const*>(grad_ptrs));
+  if (rc != GAC_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  return run_step(ctx, grad_ptrs, false, dev_sums3, ApplyKind::kPlain, nullptr,
+                  static_cast<hipStream_t>(hip_stream), host_out);
+}
+
+int gac_step_adamw(gac_ctx* ctx, void* const* grad_ptrs, float* const* master_p, float* const* m,
+                   float* const* v, void* const* p_lowp, const gac_adamw_hyper* hyper,
+                   void* hip_stream, gac_result* host_out) {
+  if (ctx == nullptr || hyper == nullptr) return GAC_ERR_INVALID_ARG;
+  int rc = check_ptrs(ctx, const_cast<const void* const*>(grad_ptrs));
+  if (rc != GAC_OK) return rc;
+  if (ctx->n_tensors > 0 && (master_p == nullptr || m == nullptr || v == nullptr)) return GAC_ERR_INVALID_ARG;
+  for (int j = 0; j < ctx->n_tensors; ++j) {
+    if (ctx->numel[j] == 0) continue;
+    if (!master_p[j] || !m[j] || !v[j]) return GAC_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(master_p[j]) | reinterpret_cast<uintptr_t>(m[j]) |
+         reinterpret_cast<uintptr_t>(v[j])) & 3u)
+      return GAC_ERR_INVALID_ARG;
+    if (p_lowp != nullptr && (p_lowp[j] == nullptr || reinterpret_cast<uintptr_t>(p_lowp[j]) %
+                                                          static_cast<uintptr_t>(elem_size(ctx->dtype))))
+      return GAC_ERR_INVALID_ARG;
+  }
+  if (hyper->t_adam < 1 || !(hyper->beta1 >= 0 && hyper->beta1 < 1) ||
+      !(hyper->beta2 >= 0 && hyper->beta2 < 1) || !(hyper->eps_adam >= 0) ||
+      !std::isfinite(hyper->lr) || !std::isfinite(hyper->weight_decay))
+    return GAC_ERR_INVALID_ARG;
+  AdamScalars h;
+  const double bc1 = 1.0 - std::pow(hyper->beta1, static_cast<double>(hyper->t_adam));
+  const double bc2 = 1.0 - std::pow(hyper->beta2, static_cast<double>(hyper->t_adam));
+  h.beta1 = static_cast<float>(hyper->beta1);
+  h.one_minus_beta1 = static_cast<float>(1.0 - hyper->beta1);
+  h.beta2 = static_cast<float>(hyper->beta2);
+  h.one_minus_beta2 = static_cast<float>(1.0 - hyper->beta2);
+  h.decay = static_cast<float>(1.0 - hyper->lr * hyper->weight_decay);
+  h.step_size = static_cast<float>(hyper->lr / bc1);
+  h.inv_sqrt_bc2 = static_cast<float>(1.0 / std::sqrt(bc2));
+  h.eps_adam = static_cast<float>(hyper->eps_adam);
+  DeviceGuard guard(ctx->device);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  rc = upload_adam(ctx, master_p, m, v, p_lowp, stream);
+  if (rc != GAC_OK) return rc;
+  return run_step(ctx, grad_ptrs, true, nullptr, ApplyKind::kAdamW, &h, stream, host_out);
+}
+
+int gac_result_device(const gac_ctx* ctx, const gac_result** dev_ptr) {
+  if (ctx == nullptr || dev_ptr == nullptr) return GAC_ERR_INVALID_ARG;
+  *dev_ptr = ctx->dev_result;
+  return GAC_OK;
+}
+
+int gac_state_export(gac_ctx* ctx, void* const* dst_ptrs, int64_t* step_out, void* hip_stream) {
+  if (ctx == nullptr) return GAC_ERR_INVALID_ARG;
+  int rc = check_ptrs(ctx, const_cast<const void* const*>(dst_ptrs));
+  if (rc != GAC_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  if (step_out) *step_out = ctx->step;
+  return state_op(ctx, gac::kStateCopy, const_cast<const void* const*>(ctx->state.data()), dst_ptrs,
+                  static_cast<hipStream_t>(hip_stream));
+}
+
+int gac_state_import(gac_ctx* ctx, void* const* src_ptrs, int64_t step, void* hip_stream) {
+  if (ctx == nullptr || step < 0) return GAC_ERR_INVALID_ARG;
+  int rc = check_ptrs(ctx, const_cast<const void* const*>(src_ptrs));
+  if (rc != GAC_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  rc = state_op(ctx, gac::kStateCopy, const_cast<const void* const*>(src_ptrs), ctx->state.data(),
+                static_cast<hipStream_t>(hip_stream));
+  if (rc == GAC_OK) ctx->step = step;
+  return rc;
+}
+
+int gac_reset(gac_ctx* ctx, void* hip_stream) {
+  if (ctx == nullptr) return GAC_ERR_INVALID_ARG;
+  DeviceGuard guard(ctx->device);
+  int rc = state_op(ctx, gac::kStateZero, nullptr, ctx->state.data(), static_cast<hipStream_t>(hip_stream));
+  if (rc == GAC_OK) ctx->step = 0;
+  return rc;
+}
+
+int gac_set_thresholds(gac_ctx* ctx, double c_low, double c_high) {
+  if (ctx == nullptr) return GAC_ERR_INVALID_ARG;
+  if (!thresholds_ok(c_low, c_high)) return GAC_ERR_BAD_THRESHOLDS;
+  ctx->c_low = c_low;
+  ctx->c_high = c_high;
+  return GAC_OK;
+}
+
+int gac_profile_enable(gac_ctx* ctx, int32_t on) {
+  if (ctx == nullptr) return GAC_ERR_INVALID_ARG;
+  ctx->profiling = on != 0;
+  ctx->prof_used = 0;
+  return GAC_OK;
+}
+
+int gac_profile_read(gac_ctx* ctx, double* ms_reduce, double* ms_finalize, double* ms_apply,
+                     int32_t* n_steps) {
+  if (ctx == nullptr) return GAC_ERR_INVALID_ARG;
+  DeviceGuard guard(ctx->device);
+  double t[3] = {0, 0, 0};
+  for (size_t i = 0; i < ctx->prof_used; ++i) {
+    StepEvents& ev = ctx->prof_pool[i];
+    GAC_HIP(ctx, hipEventSynchronize(ev.e[3]));
+    for (int k = 0; k < 3; ++k) {
+      float ms = 0.f;
+      GAC_HIP(ctx, hipEventElapsedTime(&ms, ev.e[k], ev.e[k + 1]));
+      t[k] += ms;
+    }
+  }
+  if (ms_reduce) *ms_reduce = t[0];
+  if (ms_finalize) *ms_finalize = t[1];
+  if (ms_apply) *ms_apply = t[2];
+  if (n_steps) *n_steps = static_cast<int32_t>(ctx->prof_used);
+  ctx->prof_used = 0;
+  return GAC_OK;
+}
+
+const char* gac_strerror(int code) {
+  switch (code) {
+    case GAC_OK: return "ok";
+    case GAC_ERR_INVALID_ARG: return "invalid argument";
+    case GAC_ERR_BAD_THRESHOLDS: return "thresholds must satisfy 0 < c_low < c_high, eps >= 0, beta >= 0";
+    case GAC_ERR_ALLOC: return "allocation failed";
+    case GAC_ERR_HIP: return "HIP runtime error";
+    case GAC_ERR_NONFINITE: return "non-finite gradient statistics; nothing was modified";
+    case GAC_ERR_UNIMPLEMENTED: return "not implemented";
+    default: return "unknown error code";
+  }
+}
+
+const char* gac_last_hip_error(const gac_ctx* ctx) {
+  return ctx ? ctx->hip_err.c_str() : g_last_hip_error.c_str();
+}
+
+const char* gac_version(void) { return "gac-mi355x 0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,75 @@
+// Internal interface between the host side of the library (context, planner, C ABI)
+// and its HIP kernels.  Not installed; the public interface is include/gac.h.
+#pragma once
+
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+#include "gac.h"
+
+namespace gac {
+
+// One entry per tensor plus a sentinel entry (first_chunk = total number of chunks).
+// The tensor list is cut into chunks of at most chunk_elems elements; a chunk never
+// straddles two tensors, so every chunk is one contiguous range of one g and one d.
+struct Seg {
+  const void* a;        // gradient g (reduce/apply), or source buffer (state copy)
+  void* b;              // reference state d, or destination buffer (state copy)
+  int64_t numel;
+  int64_t first_chunk;  // index of this tensor's first chunk in the global chunk order
+};
+static_assert(sizeof(Seg) == 32, "Seg layout is shared with device code");
+
+// Per-tensor optimizer buffers for the fused AdamW pass.
+struct AdamSeg {
+  float* p;
+  float* m;
+  float* v;
+  void* p_lowp;  // may be null
+};
+static_assert(sizeof(AdamSeg) == 32, "AdamSeg layout is shared with device code");
+
+// What the finalize kernel needs besides the partial sums.
+struct DecideParams {
+  double c_low, c_high, eps, beta;
+  int64_t step;
+};
+
+// AdamW scalars, prepared on the host in fp64 and rounded once to fp32.
+struct AdamScalars {
+  float beta1, one_minus_beta1;
+  float beta2, one_minus_beta2;
+  float decay;         // 1 - lr * weight_decay
+  float step_size;     // lr / (1 - beta1^t)
+  float inv_sqrt_bc2;  // 1 / sqrt(1 - beta2^t)
+  float eps_adam;
+};
+
+constexpr int kThreads = 256;             // threads per workgroup of every streaming kernel
+constexpr int kMaxGridBlocks = 1 << 16;   // upper bound on workgroups per launch (partials buffer)
+
+enum StateOp { kStateZero = 0, kStateCopy = 1 };
+
+// Launchers (defined in gac_kernels.hip).  Each validates nothing: the host side has
+// already checked shapes against the plan.  All return the launch's hipError_t.
+hipError_t launch_reduce(int dtype, const Seg* dev_segs, int64_t n_chunks, int chunk_elems,
+                         double* dev_partials, int grid, hipStream_t stream);
+
+// mode bit 0: combine partials into sums (else read sums_in); bit 1: decide and write result.
+hipError_t launch_finalize(const double* dev_partials, int n_partials, const double* sums_in,
+                           double* sums_out, gac_result* dev_result, DecideParams p, int mode,
+                           hipStream_t stream);
+
+hipError_t launch_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
+                        int chunk_elems, const gac_result* dev_result, float beta, int grid,
+                        hipStream_t stream);
+
+hipError_t launch_apply_adamw(int dtype, const Seg* dev_segs, const AdamSeg* dev_adam,
+                              int n_tensors, int64_t n_chunks, int chunk_elems,
+                              const gac_result* dev_result, float beta, AdamScalars h, int grid,
+                              hipStream_t stream);
+
+hipError_t launch_state_op(int dtype, int op, const Seg* dev_segs, int64_t n_chunks,
+                           int chunk_elems, int grid, hipStream_t stream);
+
+}  // namespace gac

@@ -1,0 +1,639 @@
+// HIP kernels of the GAC step for gfx950 (CDNA4, 64-wide wavefronts).
+//
+// The step is two streaming passes over the gradient list g and the reference state d:
+//   pass 1 (reduce_kernel)   three inner products <g,d>, <g,g>, <d,d>      (Appendix A.1)
+//   finalize_kernel          cosine with eps, regime, alpha, coefficient    (Eq. 1, Sec. 4.2)
+//   pass 2 (apply_kernel)    g <- beta g + k d in place and d <- raw g      (Eq. 4, App. A.2)
+//          (apply_adamw_kernel: the same with AdamW consuming g' in registers, Table 2)
+// Both passes are bound by HBM bandwidth (3 FMA per 2 loaded elements, 1 FMA per 4 moved
+// elements), so there is no matrix-core work here; what matters is 16-byte accesses that
+// coalesce to full cache lines, many loads in flight per wave, and all CUs busy.
+//
+// Work distribution: the tensor list is cut into chunks (gac_internal.h: Seg); workgroup b
+// of a G-wide persistent grid takes chunks b, b+G, b+2G, ...  The chunk -> workgroup map is
+// static, every workgroup writes its own partial sums, and the finalize kernel adds them in
+// index order, so results are bit-reproducible.  No floating-point atomics anywhere.
+//
+// Accumulation: products are formed and summed in fp32 over one group of at most
+// kUnroll * 8 elements per lane (for bf16 inputs each product is exact in fp32), then the
+// group sum is widened and accumulated in fp64 per lane; wave, workgroup and grid combines
+// are fp64.
+
+#include <hip/hip_runtime.h>
+
+#include "gac_internal.h"
+
+namespace gac {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// Pointers read from the tensor table are generic; casting them to the global address
+// space lets the compiler emit global_load/global_store instead of flat accesses.
+#define GAC_GLOBAL __attribute__((address_space(1)))
+typedef GAC_GLOBAL u32x4 gvec;
+typedef GAC_GLOBAL char gchar;
+typedef GAC_GLOBAL float gfloat;
+typedef GAC_GLOBAL uint32_t gu32;
+typedef GAC_GLOBAL uint16_t gu16;
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+#ifndef GAC_REDUCE_UNROLL
+#define GAC_REDUCE_UNROLL 4
+#endif
+#ifndef GAC_APPLY_UNROLL
+#define GAC_APPLY_UNROLL 4
+#endif
+#ifndef GAC_NT_LOAD
+#define GAC_NT_LOAD 0
+#endif
+#ifndef GAC_NT_STORE
+#define GAC_NT_STORE 1
+#endif
+
+template <int DT> struct Elem;
+template <> struct Elem<GAC_F32> {
+  static constexpr int kSize = 4;
+  static constexpr int kPerVec = 4;
+};
+template <> struct Elem<GAC_BF16> {
+  static constexpr int kSize = 2;
+  static constexpr int kPerVec = 8;
+};
+
+__device__ __forceinline__ u32x4 ld16(const gvec* p) {
+#if GAC_NT_LOAD
+  return __builtin_nontemporal_load(p);
+#else
+  return *p;
+#endif
+}
+
+__device__ __forceinline__ void st16(gvec* p, u32x4 v) {
+#if GAC_NT_STORE
+  __builtin_nontemporal_store(v, p);
+#else
+  *p = v;
+#endif
+}
+
+// 16 raw bytes -> fp32 values.  bf16 is the upper half of a binary32, element 0 in the
+// low half of word 0 (little endian).
+template <int DT>
+__device__ __forceinline__ void unpack(u32x4 v, float (&x)[Elem<DT>::kPerVec]) {
+  if constexpr (DT == GAC_F32) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x[i] = __uint_as_float(v[i]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[2 * i] = __uint_as_float(v[i] << 16);
+      x[2 * i + 1] = __uint_as_float(v[i] & 0xffff0000u);
+    }
+  }
+}
+
+// fp32 -> bf16 pair, round to nearest even (the hardware conversion of gfx950).
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  f32x2 f = {lo, hi};
+  bf16x2 h = __builtin_convertvector(f, bf16x2);
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+template <int DT>
+__device__ __forceinline__ u32x4 pack(const float (&x)[Elem<DT>::kPerVec]) {
+  u32x4 v;
+  if constexpr (DT == GAC_F32) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = __float_as_uint(x[i]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = pack_bf16x2(x[2 * i], x[2 * i + 1]);
+  }
+  return v;
+}
+
+template <int DT>
+__device__ __forceinline__ float load_elem(const gchar* p, int i) {
+  if constexpr (DT == GAC_F32) {
+    return reinterpret_cast<const gfloat*>(p)[i];
+  } else {
+    return __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const gu16*>(p)[i]) << 16);
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ void store_elem(gchar* p, int i, float x) {
+  if constexpr (DT == GAC_F32) {
+    reinterpret_cast<gfloat*>(p)[i] = x;
+  } else {
+    reinterpret_cast<gu16*>(p)[i] = static_cast<uint16_t>(pack_bf16x2(x, 0.0f) & 0xffffu);
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ void copy_elem(const gchar* src, gchar* dst, int i) {
+  if constexpr (DT == GAC_F32) {
+    reinterpret_cast<gu32*>(dst)[i] = reinterpret_cast<const gu32*>(src)[i];
+  } else {
+    reinterpret_cast<gu16*>(dst)[i] = reinterpret_cast<const gu16*>(src)[i];
+  }
+}
+
+// One contiguous piece of one tensor.
+struct Chunk {
+  const gchar* a;
+  gchar* b;
+  int64_t elem_off;  // offset of the chunk inside its tensor, in elements
+  int len;           // elements in this chunk (the last chunk of a tensor may be short)
+  int tensor;
+};
+
+// Finds the tensor that owns global chunk c.  `t` is a cursor that only moves in the
+// direction the caller walks the chunk order (forward: REVERSE = false).
+template <bool REVERSE>
+__device__ __forceinline__ Chunk locate(const Seg* __restrict__ segs, int& t, int64_t c,
+                                        int chunk_elems, int esize) {
+  if constexpr (REVERSE) {
+    while (c < segs[t].first_chunk) --t;
+  } else {
+    while (c >= segs[t + 1].first_chunk) ++t;
+  }
+  const Seg s = segs[t];
+  Chunk ch;
+  ch.elem_off = (c - s.first_chunk) * static_cast<int64_t>(chunk_elems);
+  const int64_t rest = s.numel - ch.elem_off;
+  ch.len = rest < chunk_elems ? static_cast<int>(rest) : chunk_elems;
+  ch.a = (const gchar*)(s.a) + ch.elem_off * esize;
+  ch.b = (gchar*)(s.b) + ch.elem_off * esize;
+  ch.tensor = t;
+  return ch;
+}
+
+__device__ __forceinline__ bool aligned16(const GAC_GLOBAL void* p) {
+  return ((uintptr_t)(p) & 15u) == 0;
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// Sum of three per-lane doubles over the workgroup; the result is valid in thread 0.
+__device__ __forceinline__ void block_sum3(double (&s)[3]) {
+  __shared__ double sm[3][kThreads / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    s[k] = wave_sum(s[k]);
+    if (lane == 0) sm[k][wave] = s[k];
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      double acc = sm[k][0];
+#pragma unroll
+      for (int w = 1; w < kThreads / 64; ++w) acc += sm[k][w];
+      s[k] = acc;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ pass 1: reduction
+
+template <int DT>
+__device__ __forceinline__ void dot3(u32x4 a, u32x4 b, float& gd, float& gg, float& dd) {
+  constexpr int N = Elem<DT>::kPerVec;
+  float x[N], y[N];
+  unpack<DT>(a, x);
+  unpack<DT>(b, y);
+#pragma unroll
+  for (int e = 0; e < N; ++e) {
+    gd = fmaf(x[e], y[e], gd);
+    gg = fmaf(x[e], x[e], gg);
+    dd = fmaf(y[e], y[e], dd);
+  }
+}
+
+template <int DT, int U>
+__global__ __launch_bounds__(kThreads) void reduce_kernel(const Seg* __restrict__ segs,
+                                                          int64_t n_chunks, int chunk_elems,
+                                                          double* __restrict__ partials) {
+  constexpr int N = Elem<DT>::kPerVec;
+  const int tid = threadIdx.x;
+  double acc[3] = {0.0, 0.0, 0.0};
+  int t = 0;
+  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    const Chunk ch = locate<false>(segs, t, c, chunk_elems, Elem<DT>::kSize);
+    if (aligned16(ch.a) && aligned16(ch.b)) {
+      const gvec* __restrict__ gv = reinterpret_cast<const gvec*>(ch.a);
+      const gvec* __restrict__ dv = reinterpret_cast<const gvec*>(ch.b);
+      const int nvec = ch.len / N;
+      int i = tid;
+      for (; i + (U - 1) * kThreads < nvec; i += U * kThreads) {
+        u32x4 a[U], b[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) a[u] = ld16(gv + i + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < U; ++u) b[u] = ld16(dv + i + u * kThreads);
+        float gd = 0.f, gg = 0.f, dd = 0.f;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          float pgd = 0.f, pgg = 0.f, pdd = 0.f;
+          dot3<DT>(a[u], b[u], pgd, pgg, pdd);
+          gd += pgd;
+          gg += pgg;
+          dd += pdd;
+        }
+        acc[0] += static_cast<double>(gd);
+        acc[1] += static_cast<double>(gg);
+        acc[2] += static_cast<double>(dd);
+      }
+      for (; i < nvec; i += kThreads) {
+        float gd = 0.f, gg = 0.f, dd = 0.f;
+        dot3<DT>(ld16(gv + i), ld16(dv + i), gd, gg, dd);
+        acc[0] += static_cast<double>(gd);
+        acc[1] += static_cast<double>(gg);
+        acc[2] += static_cast<double>(dd);
+      }
+      const int e = nvec * N + tid;  // at most N-1 leftover elements
+      if (e < ch.len) {
+        const float x = load_elem<DT>(ch.a, e), y = load_elem<DT>(ch.b, e);
+        acc[0] += static_cast<double>(x * y);
+        acc[1] += static_cast<double>(x * x);
+        acc[2] += static_cast<double>(y * y);
+      }
+    } else {
+      // element-wise path for tensors that are not 16-byte aligned
+      for (int i = tid; i < ch.len; i += kThreads) {
+        const double x = static_cast<double>(load_elem<DT>(ch.a, i));
+        const double y = static_cast<double>(load_elem<DT>(ch.b, i));
+        acc[0] = fma(x, y, acc[0]);
+        acc[1] = fma(x, x, acc[1]);
+        acc[2] = fma(y, y, acc[2]);
+      }
+    }
+  }
+  block_sum3(acc);
+  if (tid == 0) {
+    partials[3 * blockIdx.x + 0] = acc[0];
+    partials[3 * blockIdx.x + 1] = acc[1];
+    partials[3 * blockIdx.x + 2] = acc[2];
+  }
+}
+
+// ------------------------------------------------------------------ finalize
+
+// mode bit 0: add the per-workgroup partials (fixed order) instead of reading sums_in;
+// mode bit 1: evaluate the cosine and the regime and write the result record.
+__global__ __launch_bounds__(kThreads) void finalize_kernel(const double* __restrict__ partials,
+                                                            int n_partials,
+                                                            const double* __restrict__ sums_in,
+                                                            double* __restrict__ sums_out,
+                                                            gac_result* __restrict__ res,
+                                                            DecideParams p, int mode) {
+  double s[3] = {0.0, 0.0, 0.0};
+  if (mode & 1) {
+    for (int j = threadIdx.x; j < n_partials; j += kThreads) {
+      s[0] += partials[3 * j + 0];
+      s[1] += partials[3 * j + 1];
+      s[2] += partials[3 * j + 2];
+    }
+    block_sum3(s);
+  } else if (threadIdx.x == 0) {
+    s[0] = sums_in[0];
+    s[1] = sums_in[1];
+    s[2] = sums_in[2];
+  }
+  if (threadIdx.x != 0) return;
+  if (sums_out != nullptr) {
+    sums_out[0] = s[0];
+    sums_out[1] = s[1];
+    sums_out[2] = s[2];
+  }
+  if (!(mode & 2)) return;
+  const double s_gd = s[0], s_gg = s[1], s_dd = s[2];
+  gac_result r;
+  r.dot = s_gd;
+  r.gg = s_gg;
+  r.dd = s_dd;
+  r.alpha = 1.0;
+  r.coef = 0.0;
+  r.nonfinite = 0;
+  r.step = p.step;
+  if (!(isfinite(s_gd) && isfinite(s_gg) && isfinite(s_dd))) {
+    r.c = __longlong_as_double(0x7ff8000000000000LL);
+    r.regime = GAC_SKIP;
+    r.nonfinite = 1;
+  } else {
+    // Appendix A.1: eps is added to the square root of the product of the squared norms.
+    const double c = s_gd / (sqrt(s_gg * s_dd) + p.eps);
+    const double mag = fabs(c);
+    r.c = c;
+    if (mag <= p.c_low) {  // Algorithm 1 tests the safe branch first
+      r.regime = GAC_SAFE;
+    } else if (mag >= p.c_high) {
+      r.regime = GAC_SKIP;
+    } else {
+      r.regime = GAC_PROJECT;
+      r.alpha = p.c_low / mag;
+      // <g,u> u = (<g,d>/<d,d>) d, so g' = beta g + (alpha - beta)(<g,d>/<d,d>) d.
+      // |c| > c_low > 0 implies <d,d> > 0.
+      r.coef = (r.alpha - p.beta) * (s_gd / s_dd);
+    }
+  }
+  *res = r;
+}
+
+// ------------------------------------------------------------------ pass 2: apply
+
+template <int DT>
+__device__ __forceinline__ u32x4 project_vec(u32x4 a, u32x4 b, float k, float beta) {
+  constexpr int N = Elem<DT>::kPerVec;
+  float x[N], y[N];
+  unpack<DT>(a, x);
+  unpack<DT>(b, y);
+#pragma unroll
+  for (int e = 0; e < N; ++e) x[e] = fmaf(k, y[e], beta * x[e]);
+  return pack<DT>(x);
+}
+
+// Chunks are walked from the end of the list towards its start: the reduction pass has
+// just streamed the list front to back, so its last chunks are the ones most likely to
+// still sit in the last-level cache.
+template <int DT, int U>
+__global__ __launch_bounds__(kThreads) void apply_kernel(const Seg* __restrict__ segs,
+                                                         int n_tensors, int64_t n_chunks,
+                                                         int chunk_elems,
+                                                         const gac_result* __restrict__ res,
+                                                         float beta) {
+  constexpr int N = Elem<DT>::kPerVec;
+  if (res->nonfinite) return;  // convention: a non-finite step modifies nothing
+  const bool project = res->regime == GAC_PROJECT;
+  const float k = static_cast<float>(res->coef);
+  const int tid = threadIdx.x;
+  int t = n_tensors - 1;
+  for (int64_t cr = blockIdx.x; cr < n_chunks; cr += gridDim.x) {
+    const Chunk ch = locate<true>(segs, t, n_chunks - 1 - cr, chunk_elems, Elem<DT>::kSize);
+    if (aligned16(ch.a) && aligned16(ch.b)) {
+      gvec* gv = reinterpret_cast<gvec*>(const_cast<gchar*>(ch.a));
+      gvec* dv = reinterpret_cast<gvec*>(ch.b);
+      const int nvec = ch.len / N;
+      int i = tid;
+      if (project) {
+        for (; i + (U - 1) * kThreads < nvec; i += U * kThreads) {
+          u32x4 a[U], b[U];
+#pragma unroll
+          for (int u = 0; u < U; ++u) a[u] = ld16(gv + i + u * kThreads);
+#pragma unroll
+          for (int u = 0; u < U; ++u) b[u] = ld16(dv + i + u * kThreads);
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            st16(gv + i + u * kThreads, project_vec<DT>(a[u], b[u], k, beta));
+            st16(dv + i + u * kThreads, a[u]);
+          }
+        }
+        for (; i < nvec; i += kThreads) {
+          const u32x4 a = ld16(gv + i), b = ld16(dv + i);
+          st16(gv + i, project_vec<DT>(a, b, k, beta));
+          st16(dv + i, a);
+        }
+        const int e = nvec * N + tid;
+        if (e < ch.len) {
+          const float x = load_elem<DT>(ch.a, e), y = load_elem<DT>(ch.b, e);
+          copy_elem<DT>(ch.a, ch.b, e);
+          store_elem<DT>(const_cast<gchar*>(ch.a), e, fmaf(k, y, beta * x));
+        }
+      } else {
+        for (; i + (U - 1) * kThreads < nvec; i += U * kThreads) {
+          u32x4 a[U];
+#pragma unroll
+          for (int u = 0; u < U; ++u) a[u] = ld16(gv + i + u * kThreads);
+#pragma unroll
+          for (int u = 0; u < U; ++u) st16(dv + i + u * kThreads, a[u]);
+        }
+        for (; i < nvec; i += kThreads) st16(dv + i, ld16(gv + i));
+        const int e = nvec * N + tid;
+        if (e < ch.len) copy_elem<DT>(ch.a, ch.b, e);
+      }
+    } else {
+      for (int i = tid; i < ch.len; i += kThreads) {
+        if (project) {
+          const float x = load_elem<DT>(ch.a, i), y = load_elem<DT>(ch.b, i);
+          copy_elem<DT>(ch.a, ch.b, i);
+          store_elem<DT>(const_cast<gchar*>(ch.a), i, fmaf(k, y, beta * x));
+        } else {
+          copy_elem<DT>(ch.a, ch.b, i);
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ pass 2 fused with AdamW
+
+// One AdamW update of one element (decoupled weight decay), fp32, in the operation order
+//   m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;  p <- p (1 - lr wd);
+//   p <- p - (lr/(1-b1^t)) m / (sqrt(v)/sqrt(1-b2^t) + eps)
+__device__ __forceinline__ void adamw_elem(float g, float& p, float& m, float& v,
+                                           const AdamScalars& h) {
+  m = fmaf(h.beta1, m, h.one_minus_beta1 * g);
+  v = fmaf(h.beta2, v, h.one_minus_beta2 * (g * g));
+  p = p * h.decay;
+  p = p - h.step_size * m / (sqrtf(v) * h.inv_sqrt_bc2 + h.eps_adam);
+}
+
+template <int DT>
+__global__ __launch_bounds__(kThreads) void apply_adamw_kernel(
+    const Seg* __restrict__ segs, const AdamSeg* __restrict__ adam, int n_tensors,
+    int64_t n_chunks, int chunk_elems, const gac_result* __restrict__ res, float beta,
+    AdamScalars h) {
+  constexpr int N = Elem<DT>::kPerVec;
+  constexpr int R = N / 4;  // 16-byte vectors of fp32 optimizer state per gradient vector
+  if (res->nonfinite) return;
+  const int regime = res->regime;
+  const bool project = regime == GAC_PROJECT;
+  const bool skip = regime == GAC_SKIP;
+  const float k = static_cast<float>(res->coef);
+  const int tid = threadIdx.x;
+  int t = n_tensors - 1;
+  for (int64_t cr = blockIdx.x; cr < n_chunks; cr += gridDim.x) {
+    const Chunk ch = locate<true>(segs, t, n_chunks - 1 - cr, chunk_elems, Elem<DT>::kSize);
+    const AdamSeg as = adam[ch.tensor];
+    gfloat* pp = (gfloat*)(as.p) + ch.elem_off;
+    gfloat* pm = (gfloat*)(as.m) + ch.elem_off;
+    gfloat* pv = (gfloat*)(as.v) + ch.elem_off;
+    gchar* pl = as.p_lowp ? (gchar*)(as.p_lowp) + ch.elem_off * Elem<DT>::kSize : nullptr;
+    const bool vec_ok = aligned16(ch.a) && aligned16(ch.b) && aligned16(pp) && aligned16(pm) &&
+                        aligned16(pv) && aligned16(pl);
+    int first_scalar = 0;
+    if (vec_ok) {
+      const gvec* gv = reinterpret_cast<const gvec*>(ch.a);
+      gvec* dv = reinterpret_cast<gvec*>(ch.b);
+      gvec* vp = reinterpret_cast<gvec*>(pp);
+      gvec* vm = reinterpret_cast<gvec*>(pm);
+      gvec* vv = reinterpret_cast<gvec*>(pv);
+      gvec* vl = reinterpret_cast<gvec*>(pl);
+      const int nvec = ch.len / N;
+      for (int i = tid; i < nvec; i += kThreads) {
+        const u32x4 a = ld16(gv + i);
+        if (skip) {  // violation: only the reference state moves, the optimizer is untouched
+          st16(dv + i, a);
+          continue;
+        }
+        float x[N];
+        unpack<DT>(a, x);
+        if (project) {
+          float y[N];
+          unpack<DT>(ld16(dv + i), y);
+#pragma unroll
+          for (int e = 0; e < N; ++e) x[e] = fmaf(k, y[e], beta * x[e]);
+        }
+        u32x4 P[R], M[R], V[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          P[r] = ld16(vp + i * R + r);
+          M[r] = ld16(vm + i * R + r);
+          V[r] = ld16(vv + i * R + r);
+        }
+        float pnew[N];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float p = __uint_as_float(P[r][q]), m = __uint_as_float(M[r][q]),
+                  v = __uint_as_float(V[r][q]);
+            adamw_elem(x[4 * r + q], p, m, v, h);
+            P[r][q] = __float_as_uint(p);
+            M[r][q] = __float_as_uint(m);
+            V[r][q] = __float_as_uint(v);
+            pnew[4 * r + q] = p;
+          }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          st16(vp + i * R + r, P[r]);
+          st16(vm + i * R + r, M[r]);
+          st16(vv + i * R + r, V[r]);
+        }
+        st16(dv + i, a);
+        if (pl != nullptr) st16(vl + i, pack<DT>(pnew));
+      }
+      first_scalar = nvec * N;
+    }
+    for (int i = first_scalar + tid; i < ch.len; i += kThreads) {
+      if (!skip) {
+        float g = load_elem<DT>(ch.a, i);
+        if (project) g = fmaf(k, load_elem<DT>(ch.b, i), beta * g);
+        float p = pp[i], m = pm[i], v = pv[i];
+        adamw_elem(g, p, m, v, h);
+        pp[i] = p;
+        pm[i] = m;
+        pv[i] = v;
+        if (pl != nullptr) store_elem<DT>(pl, i, p);
+      }
+      copy_elem<DT>(ch.a, ch.b, i);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ state maintenance
+
+// op kStateZero: b <- 0;  op kStateCopy: b <- a.   (init / reset / export / import)
+template <int DT>
+__global__ __launch_bounds__(kThreads) void state_kernel(const Seg* __restrict__ segs,
+                                                         int64_t n_chunks, int chunk_elems,
+                                                         int op) {
+  constexpr int N = Elem<DT>::kPerVec;
+  const int tid = threadIdx.x;
+  int t = 0;
+  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    const Chunk ch = locate<false>(segs, t, c, chunk_elems, Elem<DT>::kSize);
+    const bool vec_ok = aligned16(ch.b) && (op == kStateZero || aligned16(ch.a));
+    int first_scalar = 0;
+    if (vec_ok) {
+      const gvec* src = reinterpret_cast<const gvec*>(ch.a);
+      gvec* dst = reinterpret_cast<gvec*>(ch.b);
+      const int nvec = ch.len / N;
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      for (int i = tid; i < nvec; i += kThreads) dst[i] = (op == kStateZero) ? zero : src[i];
+      first_scalar = nvec * N;
+    }
+    for (int i = first_scalar + tid; i < ch.len; i += kThreads) {
+      if (op == kStateZero) {
+        if constexpr (DT == GAC_F32) {
+          reinterpret_cast<gu32*>(ch.b)[i] = 0u;
+        } else {
+          reinterpret_cast<gu16*>(ch.b)[i] = 0u;
+        }
+      } else {
+        copy_elem<DT>(ch.a, ch.b, i);
+      }
+    }
+  }
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ launchers
+
+hipError_t launch_reduce(int dtype, const Seg* dev_segs, int64_t n_chunks, int chunk_elems,
+                         double* dev_partials, int grid, hipStream_t stream) {
+  if (dtype == GAC_F32) {
+    reduce_kernel<GAC_F32, GAC_REDUCE_UNROLL>
+        <<<grid, kThreads, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials);
+  } else {
+    reduce_kernel<GAC_BF16, GAC_REDUCE_UNROLL>
+        <<<grid, kThreads, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_finalize(const double* dev_partials, int n_partials, const double* sums_in,
+                           double* sums_out, gac_result* dev_result, DecideParams p, int mode,
+                           hipStream_t stream) {
+  finalize_kernel<<<1, kThreads, 0, stream>>>(dev_partials, n_partials, sums_in, sums_out,
+                                               dev_result, p, mode);
+  return hipGetLastError();
+}
+
+hipError_t launch_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
+                        int chunk_elems, const gac_result* dev_result, float beta, int grid,
+                        hipStream_t stream) {
+  if (dtype == GAC_F32) {
+    apply_kernel<GAC_F32, GAC_APPLY_UNROLL><<<grid, kThreads, 0, stream>>>(
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, beta);
+  } else {
+    apply_kernel<GAC_BF16, GAC_APPLY_UNROLL><<<grid, kThreads, 0, stream>>>(
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, beta);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_apply_adamw(int dtype, const Seg* dev_segs, const AdamSeg* dev_adam,
+                              int n_tensors, int64_t n_chunks, int chunk_elems,
+                              const gac_result* dev_result, float beta, AdamScalars h, int grid,
+                              hipStream_t stream) {
+  if (dtype == GAC_F32) {
+    apply_adamw_kernel<GAC_F32><<<grid, kThreads, 0, stream>>>(
+        dev_segs, dev_adam, n_tensors, n_chunks, chunk_elems, dev_result, beta, h);
+  } else {
+    apply_adamw_kernel<GAC_BF16><<<grid, kThreads, 0, stream>>>(
+        dev_segs, dev_adam, n_tensors, n_chunks, chunk_elems, dev_result, beta, h);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_state_op(int dtype, int op, const Seg* dev_segs, int64_t n_chunks,
+                           int chunk_elems, int grid, hipStream_t stream) {
+  if (dtype == GAC_F32) {
+    state_kernel<GAC_F32><<<grid, kThreads, 0, stream>>>(dev_segs, n_chunks, chunk_elems, op);
+  } else {
+    state_kernel<GAC_BF16><<<grid, kThreads, 0, stream>>>(dev_segs, n_chunks, chunk_elems, op);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace gac

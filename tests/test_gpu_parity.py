@@ -1,0 +1,331 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs, element by element (small and medium sizes; the full-size workloads are in
+test_gpu_workloads.py)."""
+import ctypes
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import gac_oracle as O
+from paper_2603_01501_amd import binding as B
+from paper_2603_01501_amd import workloads as W
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+C_LOW, C_HIGH, EPS = 0.05, 0.3, 1e-8
+DTYPES = [torch.float32, torch.bfloat16]
+
+# ragged list: 1-element tensors, an empty tensor, sizes around the 16-byte vector and the
+# chunk boundaries, one tensor spanning many chunks
+RAGGED = [(1,), (7,), (8,), (2047,), (2048,), (2049,), (0,), (32768,), (32769,), (5,), (333, 301), (4096,)]
+
+
+def make(shapes, dtype, rho, config_id=7, std=1.0):
+    g, d = W.correlated_pair(shapes, dtype, rho, std, config_id, device=DEV)
+    return g, d
+
+
+def new_ctx(shapes, dtype, state=None, **kw):
+    return B.Gac([W.numel(s) for s in shapes], U.code(dtype), state=state, **kw)
+
+
+def step_and_check(ctx, g, d, dtype, c_low=C_LOW, c_high=C_HIGH, eps=EPS, expect=None):
+    g0, d0 = U.clone_list(g), U.clone_list(d)
+    res = ctx.gac_step(g)
+    torch.cuda.synchronize()
+    dec, outs = U.check_step(res, g0, d0, g, d, dtype, c_low, c_high, eps, expect)
+    return res, dec
+
+
+# ------------------------------------------------------------------ the flat vector (N = 2^20)
+
+@pytest.mark.parametrize("c_high,expect", [(0.3, B.SKIP), (2.0, B.PROJECT)])
+def test_flat_fp32_vector(c_high, expect):
+    shapes = [(W.FLAT_N,)]
+    g, d_init = make(shapes, torch.float32, 0.9, config_id=1)
+    d = U.clone_list(d_init)
+    ctx = new_ctx(shapes, torch.float32, state=d, c_high=c_high)
+    ctx.gac_state_import(d_init, 0)  # gac_init zeroed the caller's buffers; put the reference back
+    torch.cuda.synchronize()
+    res, dec = step_and_check(ctx, g, d, torch.float32, c_high=c_high, expect=expect)
+    assert abs(res.c - 0.9) < 5 * (1 - 0.81) / math.sqrt(W.FLAT_N)
+    assert res.step == 1
+
+
+# ------------------------------------------------------------------ regimes, dtypes, ragged lists
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+@pytest.mark.parametrize("rho,expect", [(0.0, B.SAFE), (0.15, B.PROJECT), (-0.2, B.PROJECT),
+                                        (0.9, B.SKIP), (-0.6, B.SKIP)])
+@pytest.mark.parametrize("chunk_elems,grid", [(0, 0), (2048, 3)])
+def test_ragged_list_all_regimes(dtype, rho, expect, chunk_elems, grid):
+    g, d_init = make(RAGGED, dtype, rho)
+    d = U.clone_list(d_init)
+    ctx = new_ctx(RAGGED, dtype, state=d, chunk_elems=chunk_elems, grid_blocks=grid)
+    ctx.gac_state_import(d_init, 0)
+    torch.cuda.synchronize()
+    step_and_check(ctx, g, d, dtype, expect=expect)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_unaligned_tensors(dtype):
+    """Views that start 1..3 elements into an allocation: only element-aligned."""
+    sizes = [5000, 40000, 9, 2048]
+    offs = [1, 3, 2, 1]
+    g_val, d_val = make([(n,) for n in sizes], dtype, 0.15, config_id=9)
+    g_base = [torch.zeros(n + 8, dtype=dtype, device=DEV) for n in sizes]
+    d_base = [torch.zeros(n + 8, dtype=dtype, device=DEV) for n in sizes]
+    g = [b[o:o + n] for b, o, n in zip(g_base, offs, sizes)]
+    # the state is misaligned differently from the gradient in three of the tensors
+    d = [b[o2:o2 + n] for b, o2, n in zip(d_base, [1, 2, 3, 4], sizes)]
+    for view, val in zip(g + d, g_val + d_val):
+        view.copy_(val)
+    assert all(t.data_ptr() % 16 for t in g)
+    d_init = U.clone_list(d)
+    ctx = new_ctx([(n,) for n in sizes], dtype, state=d, chunk_elems=2048)
+    ctx.gac_state_import(d_init, 0)
+    torch.cuda.synchronize()
+    g_pad = U.clone_list(g_base)
+    step_and_check(ctx, g, d, dtype, expect=B.PROJECT)
+    # nothing outside the views was written
+    for b, p, o, n in zip(g_base, g_pad, offs, sizes):
+        assert U.bits_equal(b[:o], p[:o]) and U.bits_equal(b[o + n:], p[o + n:])
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_empty_inputs(dtype):
+    ctx = new_ctx([], dtype)
+    res = ctx.gac_step([])
+    assert (res.dot, res.gg, res.dd, res.c, res.regime) == (0.0, 0.0, 0.0, 0.0, B.SAFE)
+    shapes = [(0,), (0,)]
+    g = [torch.empty(0, dtype=dtype, device=DEV) for _ in shapes]
+    ctx = new_ctx(shapes, dtype)
+    res = ctx.gac_step(g)
+    assert (res.c, res.regime, res.step) == (0.0, B.SAFE, 1)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_first_step_is_safe_and_state_is_library_owned(dtype):
+    """Algorithm 1 starts from a zero reference: c = 0, safe; then the state carries."""
+    g1, _ = make(RAGGED, dtype, 0.0, config_id=11)
+    g2 = [(0.2 * a.float() + b.float()).to(dtype) for a, b in zip(g1, make(RAGGED, dtype, 0.0, config_id=12)[0])]
+    ctx = new_ctx(RAGGED, dtype)  # library allocates d
+    g1_raw = U.clone_list(g1)
+    res = ctx.gac_step(g1)
+    assert (res.c, res.regime, res.dd, res.step) == (0.0, B.SAFE, 0.0, 1)
+    out = [torch.empty_like(t) for t in g1]
+    assert ctx.gac_state_export(out) == 1
+    torch.cuda.synchronize()
+    assert all(U.bits_equal(a, b) for a, b in zip(out, g1_raw))
+    g2_raw = U.clone_list(g2)
+    res = ctx.gac_step(g2)
+    torch.cuda.synchronize()
+    U.check_step(res, g2_raw, g1_raw, g2, ctx_state(ctx, g1), dtype, C_LOW, C_HIGH, EPS, B.PROJECT)
+    assert res.step == 2
+    ctx.gac_reset()
+    res = ctx.gac_step(g1)
+    assert (res.c, res.regime, res.step) == (0.0, B.SAFE, 1)
+
+
+def ctx_state(ctx, like):
+    out = [torch.empty_like(t) for t in like]
+    ctx.gac_state_export(out)
+    torch.cuda.synchronize()
+    return out
+
+
+# ------------------------------------------------------------------ thresholds
+
+def test_threshold_boundaries_are_inclusive():
+    """|c| <= c_low is safe and |c| >= c_high is a violation: set each threshold to the very
+    cosine the GPU reports (the reduction is deterministic, so it reports it again)."""
+    shapes = [(50000,), (1234,)]
+    g, d0 = make(shapes, torch.float32, 0.2, config_id=13)
+    d = U.clone_list(d0)
+    ctx = new_ctx(shapes, torch.float32, state=d)
+
+    def run(c_low, c_high):
+        ctx.gac_state_import(d0, 0)
+        ctx.gac_set_thresholds(c_low, c_high)
+        gg = U.clone_list(g)
+        return ctx.gac_step(gg)
+
+    c = run(C_LOW, C_HIGH).c
+    assert C_LOW < c < C_HIGH
+    assert run(c, 0.9).regime == B.SAFE
+    assert run(math.nextafter(c, 0), 0.9).regime == B.PROJECT
+    assert run(0.01, c).regime == B.SKIP
+    assert run(0.01, math.nextafter(c, 1)).regime == B.PROJECT
+    with pytest.raises(B.GacError):
+        ctx.gac_set_thresholds(0.3, 0.3)
+
+
+def test_general_beta_gain():
+    """Eq. 3 with beta != 1: g' = alpha g_par + beta g_perp in the projection regime."""
+    shapes = [(30000,), (77,)]
+    g, d0 = make(shapes, torch.float32, 0.2, config_id=14)
+    d = U.clone_list(d0)
+    ctx = new_ctx(shapes, torch.float32, state=d, beta=0.5)
+    ctx.gac_state_import(d0, 0)
+    g0 = U.clone_list(g)
+    res = ctx.gac_step(g)
+    torch.cuda.synchronize()
+    assert res.regime == B.PROJECT
+    g_h, d_h = U.host_copies(g0), U.host_copies(d0)
+    s = O.sums(g_h, d_h, O.F32)
+    dec = O.decide(s, C_LOW, C_HIGH, EPS)
+    want = [O.project_decomposed(a, b, O.F32, s, dec.alpha, 0.5) for a, b in zip(g_h, d_h)]
+    assert U.rel_l2(g, want) <= 1e-5
+
+
+# ------------------------------------------------------------------ determinism, pointers, async
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_bitwise_determinism(dtype):
+    shapes = [(200000,), (65536,), (3,), (70001,)]
+    g0, d0 = make(shapes, dtype, 0.15, config_id=15)
+    d = U.clone_list(d0)
+    ctx = new_ctx(shapes, dtype, state=d)
+    first = None
+    for _ in range(10):
+        ctx.gac_state_import(d0, 0)
+        g = U.clone_list(g0)  # fresh allocations: the pointer table is uploaded again
+        res = ctx.gac_step(g)
+        torch.cuda.synchronize()
+        key = (res.dot, res.gg, res.dd, res.c, res.coef)
+        if first is None:
+            first, g_first = key, g
+        assert key == first
+        assert all(U.bits_equal(a, b) for a, b in zip(g, g_first))
+
+
+def test_async_step_and_device_result():
+    shapes = [(100000,), (4097,)]
+    g0, d0 = make(shapes, torch.bfloat16, 0.15, config_id=16)
+    d = U.clone_list(d0)
+    ctx = new_ctx(shapes, torch.bfloat16, state=d)
+    ctx.gac_state_import(d0, 0)
+    g_sync = U.clone_list(g0)
+    res = ctx.gac_step(g_sync)
+    ctx.gac_state_import(d0, 0)
+    g_async = U.clone_list(g0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    assert ctx.gac_step(g_async, stream=side, sync=False) is None
+    side.synchronize()
+    assert all(U.bits_equal(a, b) for a, b in zip(g_sync, g_async))
+    # the result record lives in device memory for callers that branch on the GPU
+    rec = B.GacResult()
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+    assert hip.hipMemcpy(ctypes.byref(rec), ctx.gac_result_device(), 64, 2) == 0  # device -> host
+    assert (rec.c, rec.regime, rec.coef) == (res.c, res.regime, res.coef) and rec.step == 1
+
+
+def test_nonfinite_gradient_modifies_nothing():
+    shapes = [(5000,), (300,)]
+    g, d0 = make(shapes, torch.float32, 0.15, config_id=17)
+    g[1][17] = float("inf")
+    d = U.clone_list(d0)
+    ctx = new_ctx(shapes, torch.float32, state=d)
+    ctx.gac_state_import(d0, 0)
+    g0 = U.clone_list(g)
+    res = B.GacResult()
+    rc = B.lib().gac_step(ctx._ctx, B.ptr_list(g), None, ctypes.byref(res))
+    torch.cuda.synchronize()
+    assert rc == B.ERR_NONFINITE and res.nonfinite == 1 and res.regime == B.SKIP and math.isnan(res.c)
+    assert all(U.bits_equal(a, b) for a, b in zip(g, g0))
+    assert all(U.bits_equal(a, b) for a, b in zip(d, d0))
+
+
+# ------------------------------------------------------------------ data-parallel two-phase form
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_two_phase_equals_one_call(dtype):
+    g0, d0 = make(RAGGED, dtype, 0.15, config_id=18)
+    d = U.clone_list(d0)
+    ctx = new_ctx(RAGGED, dtype, state=d)
+    ctx.gac_state_import(d0, 0)
+    g1 = U.clone_list(g0)
+    r1 = ctx.gac_step(g1)
+    ctx.gac_state_import(d0, 0)
+    g2 = U.clone_list(g0)
+    sums = torch.zeros(3, dtype=torch.float64, device=DEV)
+    ctx.gac_reduce_local(g2, sums)
+    r2 = ctx.gac_apply(g2, sums)
+    torch.cuda.synchronize()
+    assert sums.tolist() == [r1.dot, r1.gg, r1.dd]
+    assert (r2.c, r2.coef, r2.regime) == (r1.c, r1.coef, r1.regime)
+    assert all(U.bits_equal(a, b) for a, b in zip(g1, g2))
+
+
+@pytest.mark.parametrize("ranks", [2, 3])
+def test_sharded_ranks_emulated_on_one_gpu(ranks):
+    """Appendix A.1: every rank reduces its shard, the three scalars are summed across ranks,
+    every rank applies to its shard.  Ranks are emulated by splitting the tensor list."""
+    dtype = torch.bfloat16
+    shapes = [(40000,), (123,), (65536,), (9,), (70000,), (2048,), (31,)]
+    g0, d0 = make(shapes, dtype, 0.15, config_id=19)
+    parts = [list(range(r, len(shapes), ranks)) for r in range(ranks)]
+    gs = U.clone_list(g0)
+    ds = U.clone_list(d0)
+    ctxs, local = [], []
+    for idx in parts:
+        ctx = new_ctx([shapes[i] for i in idx], dtype, state=[ds[i] for i in idx])
+        ctx.gac_state_import([d0[i] for i in idx], 0)
+        s = torch.zeros(3, dtype=torch.float64, device=DEV)
+        ctx.gac_reduce_local([gs[i] for i in idx], s)
+        ctxs.append(ctx)
+        local.append(s)
+    total = torch.stack(local).cpu().numpy().sum(axis=0)  # rank order, fp64: the "all-reduce"
+    glob = torch.tensor(total, dtype=torch.float64, device=DEV)
+    results = [ctx.gac_apply([gs[i] for i in idx], glob) for ctx, idx in zip(ctxs, parts)]
+    torch.cuda.synchronize()
+    assert len({(r.c, r.coef, r.regime) for r in results}) == 1
+    U.check_step(results[0], g0, d0, gs, ds, dtype, C_LOW, C_HIGH, EPS, B.PROJECT)
+
+
+# ------------------------------------------------------------------ state carried over many steps
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_sixteen_ar1_steps_on_a_scaled_down_policy(dtype):
+    """The 7.6B-style list with every width divided by 28 and 2 layers, 16 consecutive AR(1)
+    steps (phi = 0.95), oracle stepped alongside; c_high = 2 forces the projection branch."""
+    model = W.scaled_down(W.MODEL_76B, 28, layers=2, vocab=3001)
+    shapes = model.tensor_shapes()
+    stream = W.AR1Stream(shapes, dtype, 0.95, 1e-3, config_id=4, device=DEV)
+    ctx = new_ctx(shapes, dtype, c_high=2.0)
+    d_oracle = [np.zeros(W.numel(s), dtype=np.uint16 if dtype == torch.bfloat16 else np.float32) for s in shapes]
+    dt = U.code(dtype)
+    n = W.total_numel(shapes)
+    for t in range(1, 17):
+        g = stream.next()
+        g_h = U.host_copies(g)
+        outs, s, dec = O.step(g_h, d_oracle, dt, C_LOW, 2.0, EPS)
+        res = ctx.gac_step(g)
+        torch.cuda.synchronize()
+        assert res.step == t and res.regime == dec.regime == (B.SAFE if t == 1 else B.PROJECT)
+        assert abs(res.c - dec.c) <= U.COS_TOL
+        if t > 1:
+            assert abs(res.c - 0.95) < 5 * (1 - 0.95 ** 2) / math.sqrt(n) + 2e-3
+            assert U.rel_l2(g, outs) <= U.GRAD_TOL[dt]
+        state = ctx_state(ctx, g)
+        for a, b in zip(state, d_oracle):
+            assert np.array_equal(W.to_oracle_array(a), b)
+
+
+def test_pointer_list_may_change_between_steps():
+    shapes = [(10000,), (555,)]
+    g1, d0 = make(shapes, torch.float32, 0.15, config_id=20)
+    d = U.clone_list(d0)
+    ctx = new_ctx(shapes, torch.float32, state=d)
+    ctx.gac_state_import(d0, 0)
+    step_and_check(ctx, g1, d, torch.float32)
+    g2 = [torch.empty_like(t).copy_(0.15 * dd + tt) for t, dd, tt in
+          zip(g1, d, make(shapes, torch.float32, 0.0, config_id=21)[0])]
+    assert g2[0].data_ptr() != g1[0].data_ptr()
+    step_and_check(ctx, g2, d, torch.float32)
