@@ -31,7 +31,8 @@ class GacConfig(ctypes.Structure):
                 ("beta", ctypes.c_double), ("dtype", ctypes.c_int32), ("n_tensors", ctypes.c_int32),
                 ("numel", ctypes.POINTER(ctypes.c_int64)), ("state_ptrs", ctypes.POINTER(ctypes.c_void_p)),
                 ("device", ctypes.c_int32), ("flags", ctypes.c_uint32),
-                ("chunk_elems", ctypes.c_int32), ("grid_blocks", ctypes.c_int32)]
+                ("chunk_elems", ctypes.c_int32), ("grid_blocks", ctypes.c_int32),
+                ("apply_blocks", ctypes.c_int32)]
 
 
 class GacResult(ctypes.Structure):
@@ -144,7 +145,7 @@ class Gac:
 
     def __init__(self, numel: Sequence[int], dtype: int, c_low: float = 0.05, c_high: float = 0.3,
                  eps: float = 1e-8, beta: float = 1.0, state: Optional[Sequence] = None,
-                 device: int = -1, chunk_elems: int = 0, grid_blocks: int = 0):
+                 device: int = -1, chunk_elems: int = 0, grid_blocks: int = 0, apply_blocks: int = 0):
         L = lib()
         cfg = GacConfig()
         L.gac_default_config(ctypes.byref(cfg))
@@ -157,6 +158,7 @@ class Gac:
         if self._state_ptrs is not None:
             cfg.state_ptrs = ctypes.cast(self._state_ptrs, ctypes.POINTER(ctypes.c_void_p))
         cfg.device, cfg.chunk_elems, cfg.grid_blocks = device, chunk_elems, grid_blocks
+        cfg.apply_blocks = apply_blocks
         self._ctx = ctypes.c_void_p()
         rc = L.gac_init(ctypes.byref(self._ctx), ctypes.byref(cfg))
         if rc != OK:

@@ -21,7 +21,6 @@ namespace {
 constexpr int kPinnedSlots = 4;         // ring of pinned staging tables for pointer uploads
 constexpr int kDefaultChunkBytes = 65536;
 constexpr int kChunkMultiple = 2048;    // chunk_elems granularity (256 threads x 8 elements)
-constexpr int kDefaultBlocksPerCU = 8;
 constexpr int kMaxProfiledSteps = 1024;
 
 int64_t elem_size(int dtype) { return dtype == GAC_BF16 ? 2 : 4; }
@@ -72,7 +71,8 @@ struct gac_ctx {
   int64_t n_chunks = 0;
   int64_t total = 0;
   int chunk_elems = 0;
-  int grid = 1;
+  int grid = 1;        // workgroups of the reduce, AdamW and state kernels (= number of partials)
+  int grid_apply = 1;  // workgroups of the apply kernel
   double c_low = 0, c_high = 0, eps = 0, beta = 1;
   int64_t step = 0;
 
@@ -271,7 +271,7 @@ int run_step(gac_ctx* ctx, void* const* grad_ptrs, bool do_reduce, const double*
   const float beta = static_cast<float>(ctx->beta);
   if (kind == ApplyKind::kPlain) {
     GAC_HIP(ctx, gac::launch_apply(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
-                                   ctx->chunk_elems, ctx->dev_result, beta, ctx->grid, stream));
+                                   ctx->chunk_elems, ctx->dev_result, beta, ctx->grid_apply, stream));
   } else {
     GAC_HIP(ctx, gac::launch_apply_adamw(ctx->dtype, ctx->dev_segs, ctx->dev_adam, ctx->n_tensors,
                                          ctx->n_chunks, ctx->chunk_elems, ctx->dev_result, beta,
@@ -316,7 +316,8 @@ int gac_init(gac_ctx** out, const gac_config* cfg) {
   if (out == nullptr) return GAC_ERR_INVALID_ARG;
   *out = nullptr;
   if (cfg == nullptr || cfg->n_tensors < 0 || (cfg->n_tensors > 0 && cfg->numel == nullptr) ||
-      cfg->flags != 0 || cfg->grid_blocks < 0 || cfg->grid_blocks > gac::kMaxGridBlocks)
+      cfg->flags != 0 || cfg->grid_blocks < 0 || cfg->grid_blocks > gac::kMaxGridBlocks ||
+      cfg->apply_blocks < 0 || cfg->apply_blocks > gac::kMaxGridBlocks)
     return GAC_ERR_INVALID_ARG;
   if (!thresholds_ok(cfg->c_low, cfg->c_high) || !(cfg->eps >= 0.0) || !(cfg->beta >= 0.0) ||
       !std::isfinite(cfg->eps) || !std::isfinite(cfg->beta))
@@ -356,12 +357,16 @@ int gac_init(gac_ctx** out, const gac_config* cfg) {
   DeviceGuard guard(dev);
   hipDeviceProp_t prop;
   GAC_HIP(ctx, hipGetDeviceProperties(&prop, dev));
-  int64_t grid = cfg->grid_blocks > 0 ? cfg->grid_blocks
-                                      : static_cast<int64_t>(prop.multiProcessorCount) * kDefaultBlocksPerCU;
-  if (grid > ctx->n_chunks) grid = ctx->n_chunks;
-  if (grid < 1) grid = 1;
-  if (grid > gac::kMaxGridBlocks) grid = gac::kMaxGridBlocks;
-  ctx->grid = static_cast<int>(grid);
+  auto pick_grid = [&](int requested, int blocks_per_cu) {
+    int64_t g = requested > 0 ? requested
+                              : static_cast<int64_t>(prop.multiProcessorCount) * blocks_per_cu;
+    if (g > ctx->n_chunks) g = ctx->n_chunks;
+    if (g < 1) g = 1;
+    if (g > gac::kMaxGridBlocks) g = gac::kMaxGridBlocks;
+    return static_cast<int>(g);
+  };
+  ctx->grid = pick_grid(cfg->grid_blocks, gac::reduce_blocks_per_cu(ctx->dtype));
+  ctx->grid_apply = pick_grid(cfg->apply_blocks, gac::apply_blocks_per_cu(ctx->dtype));
 
   ctx->state.assign(n, nullptr);
   if (cfg->state_ptrs != nullptr) {

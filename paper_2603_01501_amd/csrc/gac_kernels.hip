@@ -38,17 +38,34 @@ typedef GAC_GLOBAL uint16_t gu16;
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
+// Tuning constants (chosen from measurements on MI355X; see the measurement notes of the
+// repository).  Pass 1 is a pure read stream: 256-thread workgroups, 4 x 16 B loads per
+// array in flight per lane, non-temporal loads.  Pass 2 reads and writes the same lines: it
+// does best with few, large workgroups that load a whole 64 KiB chunk of each array and
+// then store it (1024 threads x 4 vectors), non-temporal loads and stores.
+#ifndef GAC_REDUCE_THREADS
+#define GAC_REDUCE_THREADS 256
+#endif
 #ifndef GAC_REDUCE_UNROLL
 #define GAC_REDUCE_UNROLL 4
+#endif
+#ifndef GAC_REDUCE_NT_LOAD
+#define GAC_REDUCE_NT_LOAD 1
+#endif
+#ifndef GAC_REDUCE_DOT2
+#define GAC_REDUCE_DOT2 0
+#endif
+#ifndef GAC_APPLY_THREADS
+#define GAC_APPLY_THREADS 1024
 #endif
 #ifndef GAC_APPLY_UNROLL
 #define GAC_APPLY_UNROLL 4
 #endif
-#ifndef GAC_NT_LOAD
-#define GAC_NT_LOAD 0
+#ifndef GAC_APPLY_NT_LOAD
+#define GAC_APPLY_NT_LOAD 1
 #endif
-#ifndef GAC_NT_STORE
-#define GAC_NT_STORE 1
+#ifndef GAC_APPLY_NT_STORE
+#define GAC_APPLY_NT_STORE 1
 #endif
 
 template <int DT> struct Elem;
@@ -61,20 +78,22 @@ template <> struct Elem<GAC_BF16> {
   static constexpr int kPerVec = 8;
 };
 
+template <int NT = 0>
 __device__ __forceinline__ u32x4 ld16(const gvec* p) {
-#if GAC_NT_LOAD
-  return __builtin_nontemporal_load(p);
-#else
-  return *p;
-#endif
+  if constexpr (NT) {
+    return __builtin_nontemporal_load(p);
+  } else {
+    return *p;
+  }
 }
 
+template <int NT = 1>
 __device__ __forceinline__ void st16(gvec* p, u32x4 v) {
-#if GAC_NT_STORE
-  __builtin_nontemporal_store(v, p);
-#else
-  *p = v;
-#endif
+  if constexpr (NT) {
+    __builtin_nontemporal_store(v, p);
+  } else {
+    *p = v;
+  }
 }
 
 // 16 raw bytes -> fp32 values.  bf16 is the upper half of a binary32, element 0 in the
@@ -181,8 +200,9 @@ __device__ __forceinline__ double wave_sum(double v) {
 }
 
 // Sum of three per-lane doubles over the workgroup; the result is valid in thread 0.
+template <int T>
 __device__ __forceinline__ void block_sum3(double (&s)[3]) {
-  __shared__ double sm[3][kThreads / 64];
+  __shared__ double sm[3][T / 64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
   for (int k = 0; k < 3; ++k) {
@@ -195,7 +215,7 @@ __device__ __forceinline__ void block_sum3(double (&s)[3]) {
     for (int k = 0; k < 3; ++k) {
       double acc = sm[k][0];
 #pragma unroll
-      for (int w = 1; w < kThreads / 64; ++w) acc += sm[k][w];
+      for (int w = 1; w < T / 64; ++w) acc += sm[k][w];
       s[k] = acc;
     }
   }
@@ -205,6 +225,20 @@ __device__ __forceinline__ void block_sum3(double (&s)[3]) {
 
 template <int DT>
 __device__ __forceinline__ void dot3(u32x4 a, u32x4 b, float& gd, float& gg, float& dd) {
+#if GAC_REDUCE_DOT2
+  if constexpr (DT == GAC_BF16) {
+    // two bf16 products and the running sum in one instruction per statistic
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const bf16x2 x = __builtin_bit_cast(bf16x2, a[i]);
+      const bf16x2 y = __builtin_bit_cast(bf16x2, b[i]);
+      gd = __builtin_amdgcn_fdot2_f32_bf16(x, y, gd, false);
+      gg = __builtin_amdgcn_fdot2_f32_bf16(x, x, gg, false);
+      dd = __builtin_amdgcn_fdot2_f32_bf16(y, y, dd, false);
+    }
+    return;
+  }
+#endif
   constexpr int N = Elem<DT>::kPerVec;
   float x[N], y[N];
   unpack<DT>(a, x);
@@ -217,27 +251,36 @@ __device__ __forceinline__ void dot3(u32x4 a, u32x4 b, float& gd, float& gg, flo
   }
 }
 
-template <int DT, int U>
-__global__ __launch_bounds__(kThreads) void reduce_kernel(const Seg* __restrict__ segs,
+template <int DT, int T, int U>
+__global__ __launch_bounds__(T) void reduce_kernel(const Seg* __restrict__ segs,
                                                           int64_t n_chunks, int chunk_elems,
                                                           double* __restrict__ partials) {
   constexpr int N = Elem<DT>::kPerVec;
   const int tid = threadIdx.x;
   double acc[3] = {0.0, 0.0, 0.0};
   int t = 0;
-  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
-    const Chunk ch = locate<false>(segs, t, c, chunk_elems, Elem<DT>::kSize);
+  int64_t c = blockIdx.x;
+  bool more = c < n_chunks;
+  Chunk next = {};
+  if (more) next = locate<false>(segs, t, c, chunk_elems, Elem<DT>::kSize);
+  while (more) {
+    const Chunk ch = next;
+    // Look up the following chunk now: its dependent scalar loads from the tensor table
+    // then overlap this chunk's streaming instead of stalling the workgroup between chunks.
+    c += gridDim.x;
+    more = c < n_chunks;
+    if (more) next = locate<false>(segs, t, c, chunk_elems, Elem<DT>::kSize);
     if (aligned16(ch.a) && aligned16(ch.b)) {
       const gvec* __restrict__ gv = reinterpret_cast<const gvec*>(ch.a);
       const gvec* __restrict__ dv = reinterpret_cast<const gvec*>(ch.b);
       const int nvec = ch.len / N;
       int i = tid;
-      for (; i + (U - 1) * kThreads < nvec; i += U * kThreads) {
+      for (; i + (U - 1) * T < nvec; i += U * T) {
         u32x4 a[U], b[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) a[u] = ld16(gv + i + u * kThreads);
+        for (int u = 0; u < U; ++u) a[u] = ld16<GAC_REDUCE_NT_LOAD>(gv + i + u * T);
 #pragma unroll
-        for (int u = 0; u < U; ++u) b[u] = ld16(dv + i + u * kThreads);
+        for (int u = 0; u < U; ++u) b[u] = ld16<GAC_REDUCE_NT_LOAD>(dv + i + u * T);
         float gd = 0.f, gg = 0.f, dd = 0.f;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -251,9 +294,9 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(const Seg* __restrict_
         acc[1] += static_cast<double>(gg);
         acc[2] += static_cast<double>(dd);
       }
-      for (; i < nvec; i += kThreads) {
+      for (; i < nvec; i += T) {
         float gd = 0.f, gg = 0.f, dd = 0.f;
-        dot3<DT>(ld16(gv + i), ld16(dv + i), gd, gg, dd);
+        dot3<DT>(ld16<GAC_REDUCE_NT_LOAD>(gv + i), ld16<GAC_REDUCE_NT_LOAD>(dv + i), gd, gg, dd);
         acc[0] += static_cast<double>(gd);
         acc[1] += static_cast<double>(gg);
         acc[2] += static_cast<double>(dd);
@@ -267,7 +310,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(const Seg* __restrict_
       }
     } else {
       // element-wise path for tensors that are not 16-byte aligned
-      for (int i = tid; i < ch.len; i += kThreads) {
+      for (int i = tid; i < ch.len; i += T) {
         const double x = static_cast<double>(load_elem<DT>(ch.a, i));
         const double y = static_cast<double>(load_elem<DT>(ch.b, i));
         acc[0] = fma(x, y, acc[0]);
@@ -276,7 +319,7 @@ __global__ __launch_bounds__(kThreads) void reduce_kernel(const Seg* __restrict_
       }
     }
   }
-  block_sum3(acc);
+  block_sum3<T>(acc);
   if (tid == 0) {
     partials[3 * blockIdx.x + 0] = acc[0];
     partials[3 * blockIdx.x + 1] = acc[1];
@@ -301,7 +344,7 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const double* __rest
       s[1] += partials[3 * j + 1];
       s[2] += partials[3 * j + 2];
     }
-    block_sum3(s);
+    block_sum3<kThreads>(s);
   } else if (threadIdx.x == 0) {
     s[0] = sums_in[0];
     s[1] = sums_in[1];
@@ -360,11 +403,61 @@ __device__ __forceinline__ u32x4 project_vec(u32x4 a, u32x4 b, float k, float be
   return pack<DT>(x);
 }
 
+// The part of a chunk that is not handled by the whole-tile fast path: any length, any
+// element alignment.
+template <int DT, int T, int U>
+__device__ __forceinline__ void apply_chunk_generic(const Chunk& ch, bool project, float k,
+                                                    float beta) {
+  constexpr int N = Elem<DT>::kPerVec;
+  const int tid = threadIdx.x;
+  gchar* ga = const_cast<gchar*>(ch.a);
+  if (aligned16(ch.a) && aligned16(ch.b)) {
+    gvec* gv = reinterpret_cast<gvec*>(ga);
+    gvec* dv = reinterpret_cast<gvec*>(ch.b);
+    const int nvec = ch.len / N;
+    if (project) {
+      for (int i = tid; i < nvec; i += T) {
+        const u32x4 a = ld16<GAC_APPLY_NT_LOAD>(gv + i), b = ld16<GAC_APPLY_NT_LOAD>(dv + i);
+        st16<GAC_APPLY_NT_STORE>(gv + i, project_vec<DT>(a, b, k, beta));
+        st16<GAC_APPLY_NT_STORE>(dv + i, a);
+      }
+      const int e = nvec * N + tid;  // at most N-1 leftover elements
+      if (e < ch.len) {
+        const float x = load_elem<DT>(ch.a, e), y = load_elem<DT>(ch.b, e);
+        copy_elem<DT>(ch.a, ch.b, e);
+        store_elem<DT>(ga, e, fmaf(k, y, beta * x));
+      }
+    } else {
+      for (int i = tid; i < nvec; i += T) st16<GAC_APPLY_NT_STORE>(dv + i, ld16<GAC_APPLY_NT_LOAD>(gv + i));
+      const int e = nvec * N + tid;
+      if (e < ch.len) copy_elem<DT>(ch.a, ch.b, e);
+    }
+  } else {
+    for (int i = tid; i < ch.len; i += T) {
+      if (project) {
+        const float x = load_elem<DT>(ch.a, i), y = load_elem<DT>(ch.b, i);
+        copy_elem<DT>(ch.a, ch.b, i);
+        store_elem<DT>(ga, i, fmaf(k, y, beta * x));
+      } else {
+        copy_elem<DT>(ch.a, ch.b, i);
+      }
+    }
+  }
+}
+
+// Pass 2.  A workgroup of T lanes owns one chunk at a time.  A "whole tile" is an aligned
+// chunk of exactly T*U vectors per array (the default chunk size): each lane then holds U
+// vectors of g and of d in registers, so the whole chunk is read before any of it is
+// written, and the loads of the workgroup's NEXT whole tile are issued before the current
+// one is computed and stored (two register tiles), which keeps reads in flight during the
+// arithmetic and the stores.  Other chunks (tensor tails, unaligned tensors) take the
+// generic path.
+//
 // Chunks are walked from the end of the list towards its start: the reduction pass has
 // just streamed the list front to back, so its last chunks are the ones most likely to
 // still sit in the last-level cache.
-template <int DT, int U>
-__global__ __launch_bounds__(kThreads) void apply_kernel(const Seg* __restrict__ segs,
+template <int DT, int T, int U>
+__global__ __launch_bounds__(T) void apply_kernel(const Seg* __restrict__ segs,
                                                          int n_tensors, int64_t n_chunks,
                                                          int chunk_elems,
                                                          const gac_result* __restrict__ res,
@@ -374,61 +467,65 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const Seg* __restrict__
   const bool project = res->regime == GAC_PROJECT;
   const float k = static_cast<float>(res->coef);
   const int tid = threadIdx.x;
-  int t = n_tensors - 1;
-  for (int64_t cr = blockIdx.x; cr < n_chunks; cr += gridDim.x) {
-    const Chunk ch = locate<true>(segs, t, n_chunks - 1 - cr, chunk_elems, Elem<DT>::kSize);
-    if (aligned16(ch.a) && aligned16(ch.b)) {
-      gvec* gv = reinterpret_cast<gvec*>(const_cast<gchar*>(ch.a));
-      gvec* dv = reinterpret_cast<gvec*>(ch.b);
-      const int nvec = ch.len / N;
-      int i = tid;
-      if (project) {
-        for (; i + (U - 1) * kThreads < nvec; i += U * kThreads) {
-          u32x4 a[U], b[U];
+
+  struct Tile {
+    u32x4 a[U], b[U];
+  };
+  auto whole = [&](const Chunk& ch) {
+    return ch.len == T * U * N && aligned16(ch.a) && aligned16(ch.b);
+  };
+  auto load_tile = [&](const Chunk& ch, Tile& tl) {
+    const gvec* gv = reinterpret_cast<const gvec*>(ch.a) + tid;
+    const gvec* dv = reinterpret_cast<const gvec*>(ch.b) + tid;
 #pragma unroll
-          for (int u = 0; u < U; ++u) a[u] = ld16(gv + i + u * kThreads);
+    for (int u = 0; u < U; ++u) tl.a[u] = ld16<GAC_APPLY_NT_LOAD>(gv + u * T);
+    if (project) {
 #pragma unroll
-          for (int u = 0; u < U; ++u) b[u] = ld16(dv + i + u * kThreads);
+      for (int u = 0; u < U; ++u) tl.b[u] = ld16<GAC_APPLY_NT_LOAD>(dv + u * T);
+    }
+  };
+  auto store_tile = [&](const Chunk& ch, const Tile& tl) {
+    gvec* gv = reinterpret_cast<gvec*>(const_cast<gchar*>(ch.a)) + tid;
+    gvec* dv = reinterpret_cast<gvec*>(ch.b) + tid;
+    if (project) {
 #pragma unroll
-          for (int u = 0; u < U; ++u) {
-            st16(gv + i + u * kThreads, project_vec<DT>(a[u], b[u], k, beta));
-            st16(dv + i + u * kThreads, a[u]);
-          }
-        }
-        for (; i < nvec; i += kThreads) {
-          const u32x4 a = ld16(gv + i), b = ld16(dv + i);
-          st16(gv + i, project_vec<DT>(a, b, k, beta));
-          st16(dv + i, a);
-        }
-        const int e = nvec * N + tid;
-        if (e < ch.len) {
-          const float x = load_elem<DT>(ch.a, e), y = load_elem<DT>(ch.b, e);
-          copy_elem<DT>(ch.a, ch.b, e);
-          store_elem<DT>(const_cast<gchar*>(ch.a), e, fmaf(k, y, beta * x));
-        }
-      } else {
-        for (; i + (U - 1) * kThreads < nvec; i += U * kThreads) {
-          u32x4 a[U];
-#pragma unroll
-          for (int u = 0; u < U; ++u) a[u] = ld16(gv + i + u * kThreads);
-#pragma unroll
-          for (int u = 0; u < U; ++u) st16(dv + i + u * kThreads, a[u]);
-        }
-        for (; i < nvec; i += kThreads) st16(dv + i, ld16(gv + i));
-        const int e = nvec * N + tid;
-        if (e < ch.len) copy_elem<DT>(ch.a, ch.b, e);
+      for (int u = 0; u < U; ++u) {
+        st16<GAC_APPLY_NT_STORE>(gv + u * T, project_vec<DT>(tl.a[u], tl.b[u], k, beta));
+        st16<GAC_APPLY_NT_STORE>(dv + u * T, tl.a[u]);
       }
     } else {
-      for (int i = tid; i < ch.len; i += kThreads) {
-        if (project) {
-          const float x = load_elem<DT>(ch.a, i), y = load_elem<DT>(ch.b, i);
-          copy_elem<DT>(ch.a, ch.b, i);
-          store_elem<DT>(const_cast<gchar*>(ch.a), i, fmaf(k, y, beta * x));
-        } else {
-          copy_elem<DT>(ch.a, ch.b, i);
-        }
-      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) st16<GAC_APPLY_NT_STORE>(dv + u * T, tl.a[u]);
     }
+  };
+
+  int t = n_tensors - 1;
+  int64_t cr = blockIdx.x;
+  if (cr >= n_chunks) return;
+  Chunk cur = locate<true>(segs, t, n_chunks - 1 - cr, chunk_elems, Elem<DT>::kSize);
+  bool cur_whole = whole(cur);
+  Tile tc = {};
+  if (cur_whole) load_tile(cur, tc);
+  for (;;) {
+    cr += gridDim.x;
+    const bool more = cr < n_chunks;
+    Chunk next = cur;
+    bool next_whole = false;
+    Tile tn = {};
+    if (more) {
+      next = locate<true>(segs, t, n_chunks - 1 - cr, chunk_elems, Elem<DT>::kSize);
+      next_whole = whole(next);
+      if (next_whole) load_tile(next, tn);
+    }
+    if (cur_whole) {
+      store_tile(cur, tc);
+    } else {
+      apply_chunk_generic<DT, T, U>(cur, project, k, beta);
+    }
+    if (!more) break;
+    cur = next;
+    cur_whole = next_whole;
+    tc = tn;
   }
 }
 
@@ -577,16 +674,37 @@ __global__ __launch_bounds__(kThreads) void state_kernel(const Seg* __restrict__
 
 }  // namespace
 
+// Workgroups of each kernel that fit on one CU at the same time (registers, LDS, threads).
+int reduce_blocks_per_cu(int dtype) {
+  int n = 0;
+  hipError_t e = dtype == GAC_F32
+      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(
+            &n, reduce_kernel<GAC_F32, GAC_REDUCE_THREADS, GAC_REDUCE_UNROLL>, GAC_REDUCE_THREADS, 0)
+      : hipOccupancyMaxActiveBlocksPerMultiprocessor(
+            &n, reduce_kernel<GAC_BF16, GAC_REDUCE_THREADS, GAC_REDUCE_UNROLL>, GAC_REDUCE_THREADS, 0);
+  return (e == hipSuccess && n > 0) ? n : 1;
+}
+
+int apply_blocks_per_cu(int dtype) {
+  int n = 0;
+  hipError_t e = dtype == GAC_F32
+      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(
+            &n, apply_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL>, GAC_APPLY_THREADS, 0)
+      : hipOccupancyMaxActiveBlocksPerMultiprocessor(
+            &n, apply_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL>, GAC_APPLY_THREADS, 0);
+  return (e == hipSuccess && n > 0) ? n : 1;
+}
+
 // ------------------------------------------------------------------ launchers
 
 hipError_t launch_reduce(int dtype, const Seg* dev_segs, int64_t n_chunks, int chunk_elems,
                          double* dev_partials, int grid, hipStream_t stream) {
   if (dtype == GAC_F32) {
-    reduce_kernel<GAC_F32, GAC_REDUCE_UNROLL>
-        <<<grid, kThreads, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials);
+    reduce_kernel<GAC_F32, GAC_REDUCE_THREADS, GAC_REDUCE_UNROLL>
+        <<<grid, GAC_REDUCE_THREADS, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials);
   } else {
-    reduce_kernel<GAC_BF16, GAC_REDUCE_UNROLL>
-        <<<grid, kThreads, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials);
+    reduce_kernel<GAC_BF16, GAC_REDUCE_THREADS, GAC_REDUCE_UNROLL>
+        <<<grid, GAC_REDUCE_THREADS, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials);
   }
   return hipGetLastError();
 }
@@ -603,10 +721,10 @@ hipError_t launch_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n
                         int chunk_elems, const gac_result* dev_result, float beta, int grid,
                         hipStream_t stream) {
   if (dtype == GAC_F32) {
-    apply_kernel<GAC_F32, GAC_APPLY_UNROLL><<<grid, kThreads, 0, stream>>>(
+    apply_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
         dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, beta);
   } else {
-    apply_kernel<GAC_BF16, GAC_APPLY_UNROLL><<<grid, kThreads, 0, stream>>>(
+    apply_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
         dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, beta);
   }
   return hipGetLastError();

@@ -151,12 +151,15 @@ class AR1Stream:
 
 def to_oracle_array(t: torch.Tensor) -> np.ndarray:
     """Host copy of a tensor in the layout the CPU oracle reads: float32 values, or the
-    raw bfloat16 bit patterns as uint16.  Always a fresh flat contiguous array."""
+    raw bfloat16 bit patterns as uint16.  Always a flat contiguous array that shares no
+    memory with ``t`` (the oracle overwrites state arrays in place)."""
     c = t.detach().to("cpu").contiguous().reshape(-1)
+    if not t.is_cuda:
+        c = c.clone()
     if c.dtype == torch.bfloat16:
-        return c.view(torch.int16).numpy().view(np.uint16).copy()
+        return c.view(torch.int16).numpy().view(np.uint16)
     if c.dtype == torch.float32:
-        return c.numpy().copy()
+        return c.numpy()
     raise TypeError(f"unsupported dtype {c.dtype}")
 
 

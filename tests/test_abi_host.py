@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(B.GacResult) == 64
     assert ctypes.sizeof(B.GacAdamWHyper) == 48
-    assert ctypes.sizeof(B.GacConfig) == 72
+    assert ctypes.sizeof(B.GacConfig) == 80
 
 
 def test_default_config_is_the_papers():

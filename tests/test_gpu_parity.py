@@ -65,7 +65,7 @@ def test_flat_fp32_vector(c_high, expect):
 def test_ragged_list_all_regimes(dtype, rho, expect, chunk_elems, grid):
     g, d_init = make(RAGGED, dtype, rho)
     d = U.clone_list(d_init)
-    ctx = new_ctx(RAGGED, dtype, state=d, chunk_elems=chunk_elems, grid_blocks=grid)
+    ctx = new_ctx(RAGGED, dtype, state=d, chunk_elems=chunk_elems, grid_blocks=grid, apply_blocks=grid)
     ctx.gac_state_import(d_init, 0)
     torch.cuda.synchronize()
     step_and_check(ctx, g, d, dtype, expect=expect)
