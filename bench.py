@@ -39,6 +39,11 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--grid-blocks", type=int, default=0)
+    ap.add_argument("--apply-blocks", type=int, default=0)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the steps, run one plain copy of known size (gac_state_export of "
+                         "the whole state: N*s bytes read, N*s written) so that a counter "
+                         "profile of this command can scale its byte counters")
     return ap.parse_args()
 
 
@@ -76,12 +81,14 @@ def recorded_traffic(kernel_src_sha):
 
 def timed_steps(ctx, stream, g, n_steps, torch):
     """Runs n_steps GAC steps; returns (per-step wall ms list, last result)."""
+    from paper_2603_01501_amd import binding as B
     ms, res = [], None
+    g_ptrs = B.ptr_list(g)              # the gradient buffers do not move between steps
     for _ in range(n_steps):
         stream.next_into(g)             # untimed: the next gradient of the AR(1) stream
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        res = ctx.gac_step(g)           # waits for the regime, like a training loop would
+        res = ctx.gac_step(g_ptrs)      # waits for the regime, like a training loop would
         torch.cuda.synchronize()
         ms.append((time.perf_counter() - t0) * 1e3)
     return ms, res
@@ -104,14 +111,20 @@ def cpu_baseline(shapes, dtype, torch):
     del g, d
     torch.cuda.empty_cache()
     code = B.torch_dtype_code(dtype)
-    t0 = time.perf_counter()
-    _, _, dec = O.step(g_h, d_h, code, 0.05, 0.3, 1e-8)
-    dt = time.perf_counter() - t0
+    # repeat the step on the same sample until about 10 s of CPU work have been timed
+    reps, total = 0, 0.0
+    while total < 10.0 and reps < 8:
+        d_run = [a.copy() for a in d_h]  # the oracle overwrites the state in place
+        t0 = time.perf_counter()
+        _, _, dec = O.step(g_h, d_run, code, 0.05, 0.3, 1e-8)
+        total += time.perf_counter() - t0
+        reps += 1
+        assert dec.regime == O.PROJECT
+    dt = total / reps
     es = 2 if dtype == torch.bfloat16 else 4
-    assert dec.regime == O.PROJECT
     return {"value": 6.0 * n * es / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"one projection-regime step on the first {len(take)} tensors of the list "
-                      f"({n} elements), {dt:.1f} s single-threaded",
+                      f"({n} elements), mean of {reps} runs, {dt:.1f} s each, single-threaded",
             "ms_per_step_extrapolated": dt * 1e3 * (sum(W.numel(s) for s in shapes) / n),
             "host_cpus": os.cpu_count()}
 
@@ -141,13 +154,16 @@ def main():
 
     def run(c_high, warmup, steps):
         ctx = B.Gac(numel, code, c_low=0.05, c_high=c_high, chunk_elems=args.chunk_elems,
-                    grid_blocks=args.grid_blocks)
+                    grid_blocks=args.grid_blocks, apply_blocks=args.apply_blocks)
         # step 1 meets a zero reference and is always safe; it is part of the warm-up
         timed_steps(ctx, stream, g, 1 + warmup, torch)
         ctx.gac_profile_enable(True)
         ms, res = timed_steps(ctx, stream, g, steps, torch)
         k_red, k_fin, k_app, n = ctx.gac_profile_read()
         ctx.gac_profile_enable(False)
+        if args.calibration_copy:
+            ctx.gac_state_export(g)
+            torch.cuda.synchronize()
         ctx.close()
         torch.cuda.empty_cache()
         return ms, res, (k_red / n, k_fin / n, k_app / n)

@@ -115,8 +115,8 @@ def torch_dtype_code(dtype) -> int:
 
 def ptr_list(tensors: Optional[Sequence]) -> Optional[ctypes.Array]:
     """Host array of the tensors' device pointers (tensors must be contiguous)."""
-    if tensors is None:
-        return None
+    if tensors is None or isinstance(tensors, ctypes.Array):
+        return tensors  # an array built earlier by this function is passed through
     for t in tensors:
         if not t.is_contiguous():
             raise ValueError("tensors must be contiguous")

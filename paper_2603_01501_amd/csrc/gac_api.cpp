@@ -95,7 +95,8 @@ struct gac_ctx {
   double* dev_partials = nullptr;  // 3 doubles per workgroup
   double* dev_sums = nullptr;      // 3 doubles
   gac_result* dev_result = nullptr;
-  gac_result* pinned_result = nullptr;
+  gac_result* pinned_result = nullptr;      // host address of the pinned result record
+  gac_result* pinned_result_dev = nullptr;  // the same memory as the device addresses it
   hipEvent_t result_event = nullptr;
 
   bool profiling = false;
@@ -211,11 +212,9 @@ StepEvents* next_events(gac_ctx* ctx) {
   return &ctx->prof_pool[ctx->prof_used++];
 }
 
-// Copies the device result to the host and waits for it.  The copy is ordered after the
-// finalize kernel only, so the host learns the regime while the apply kernel still runs.
-int fetch_result(gac_ctx* ctx, hipStream_t stream) {
-  GAC_HIP(ctx, hipMemcpyAsync(ctx->pinned_result, ctx->dev_result, sizeof(gac_result),
-                              hipMemcpyDeviceToHost, stream));
+// The finalize kernel writes the result record into pinned host memory itself; an event
+// recorded right after it lets the host learn the regime while the apply kernel still runs.
+int mark_result(gac_ctx* ctx, hipStream_t stream) {
   GAC_HIP(ctx, hipEventRecord(ctx->result_event, stream));
   return GAC_OK;
 }
@@ -262,9 +261,10 @@ int run_step(gac_ctx* ctx, void* const* grad_ptrs, bool do_reduce, const double*
   }
   if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[1], stream));
   GAC_HIP(ctx, gac::launch_finalize(ctx->dev_partials, ctx->grid, sums_in, ctx->dev_sums,
-                                    ctx->dev_result, decide_params(ctx), mode, stream));
+                                    ctx->dev_result, host_out ? ctx->pinned_result_dev : nullptr,
+                                    decide_params(ctx), mode, stream));
   if (host_out != nullptr) {
-    rc = fetch_result(ctx, stream);
+    rc = mark_result(ctx, stream);
     if (rc != GAC_OK) return rc;
   }
   if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[2], stream));
@@ -404,7 +404,10 @@ int gac_init(gac_ctx** out, const gac_config* cfg) {
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_partials), sizeof(double) * 3 * ctx->grid));
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_sums), sizeof(double) * 3));
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_result), sizeof(gac_result)));
-  GAC_HIP(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned_result), sizeof(gac_result), hipHostMallocDefault));
+  GAC_HIP(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned_result), sizeof(gac_result),
+                             hipHostMallocMapped));
+  GAC_HIP(ctx, hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->pinned_result_dev),
+                                       ctx->pinned_result, 0));
   GAC_HIP(ctx, hipEventCreateWithFlags(&ctx->result_event, hipEventDisableTiming));
   std::memset(ctx->pinned_result, 0, sizeof(gac_result));
 
@@ -462,7 +465,7 @@ int gac_reduce_local(gac_ctx* ctx, void* const* grad_ptrs, void* hip_stream, dou
   GAC_HIP(ctx, gac::launch_reduce(ctx->dtype, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
                                   ctx->dev_partials, ctx->grid, stream));
   GAC_HIP(ctx, gac::launch_finalize(ctx->dev_partials, ctx->grid, nullptr, dev_sums3, ctx->dev_result,
-                                    decide_params(ctx), /*mode=*/1, stream));
+                                    nullptr, decide_params(ctx), /*mode=*/1, stream));
   return GAC_OK;
 }
 

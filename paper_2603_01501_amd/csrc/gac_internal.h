@@ -60,10 +60,11 @@ int apply_blocks_per_cu(int dtype);
 hipError_t launch_reduce(int dtype, const Seg* dev_segs, int64_t n_chunks, int chunk_elems,
                          double* dev_partials, int grid, hipStream_t stream);
 
-// mode bit 0: combine partials into sums (else read sums_in); bit 1: decide and write result.
+// mode bit 0: combine partials into sums (else read sums_in); bit 1: decide and write result
+// to dev_result and, if not null, also to host_result (host-mapped pinned memory).
 hipError_t launch_finalize(const double* dev_partials, int n_partials, const double* sums_in,
-                           double* sums_out, gac_result* dev_result, DecideParams p, int mode,
-                           hipStream_t stream);
+                           double* sums_out, gac_result* dev_result, gac_result* host_result,
+                           DecideParams p, int mode, hipStream_t stream);
 
 hipError_t launch_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
                         int chunk_elems, const gac_result* dev_result, float beta, int grid,

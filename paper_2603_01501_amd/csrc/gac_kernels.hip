@@ -336,6 +336,7 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const double* __rest
                                                             const double* __restrict__ sums_in,
                                                             double* __restrict__ sums_out,
                                                             gac_result* __restrict__ res,
+                                                            gac_result* __restrict__ host_res,
                                                             DecideParams p, int mode) {
   double s[3] = {0.0, 0.0, 0.0};
   if (mode & 1) {
@@ -388,6 +389,9 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const double* __rest
     }
   }
   *res = r;
+  // Optional second copy straight into host-mapped pinned memory: the host then learns the
+  // regime by waiting on an event after this kernel, with no copy command in the stream.
+  if (host_res != nullptr) *host_res = r;
 }
 
 // ------------------------------------------------------------------ pass 2: apply
@@ -710,10 +714,10 @@ hipError_t launch_reduce(int dtype, const Seg* dev_segs, int64_t n_chunks, int c
 }
 
 hipError_t launch_finalize(const double* dev_partials, int n_partials, const double* sums_in,
-                           double* sums_out, gac_result* dev_result, DecideParams p, int mode,
-                           hipStream_t stream) {
+                           double* sums_out, gac_result* dev_result, gac_result* host_result,
+                           DecideParams p, int mode, hipStream_t stream) {
   finalize_kernel<<<1, kThreads, 0, stream>>>(dev_partials, n_partials, sums_in, sums_out,
-                                               dev_result, p, mode);
+                                               dev_result, host_result, p, mode);
   return hipGetLastError();
 }
 
