@@ -35,7 +35,8 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=15)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="7.6B", choices=["7.6B", "1.5B", "0.5B", "flat"])
+    ap.add_argument("--workload", default="7.6B",
+                    choices=["7.6B", "1.5B", "0.5B", "flat", "14B-adamw", "7.6B-adamw", "1.5B-adamw"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--grid-blocks", type=int, default=0)
@@ -129,6 +130,76 @@ def cpu_baseline(shapes, dtype, torch):
             "host_cpus": os.cpu_count()}
 
 
+def main_adamw(args):
+    """GAC fused with AdamW (gac_step_adamw) on a bf16 gradient list with fp32 m, v and master
+    parameters.  Consecutive gradients are g_t = 0.9 d + sqrt(1 - 0.81) std n_t, where d is the
+    reference state (the previous raw gradient), generated between steps outside the timed
+    region; thresholds (0.05, 2.0) so that the projection branch and the optimizer both run."""
+    import math
+    import torch
+    from paper_2603_01501_amd import binding as B
+    from paper_2603_01501_amd import workloads as W
+    model = {"14B-adamw": W.MODEL_14B, "7.6B-adamw": W.MODEL_76B, "1.5B-adamw": W.MODEL_15B}[args.workload]
+    shapes = model.tensor_shapes()
+    numel = [W.numel(s) for s in shapes]
+    N = sum(numel)
+    dev = "cuda:0"
+    dtype = torch.bfloat16
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(W.tensor_seed(5, 0))
+    d = [torch.empty(s, dtype=dtype, device=dev) for s in shapes]
+    g = [torch.empty(s, dtype=dtype, device=dev) for s in shapes]
+    p, m, v = [], [], []
+    for s in shapes:
+        p.append(torch.randn(s, generator=gen, device=dev).mul_(0.02))
+        m.append(torch.randn(s, generator=gen, device=dev).mul_(1e-4))
+        v.append(torch.rand(s, generator=gen, device=dev).mul_(1e-6))
+
+    def next_gradient(first):
+        w = math.sqrt(1.0 - 0.81) * 1e-3
+        for gj, dj in zip(g, d):
+            z = torch.randn(gj.shape, generator=gen, device=dev, dtype=torch.float32)
+            if first:
+                gj.copy_(z.mul_(1e-3))
+            else:
+                gj.copy_(z.mul_(w).add_(dj.float(), alpha=0.9))
+            del z
+
+    ctx = B.Gac(numel, B.BF16, c_low=0.05, c_high=2.0, state=d, chunk_elems=args.chunk_elems,
+                grid_blocks=args.grid_blocks, apply_blocks=args.apply_blocks)
+    ptrs = [B.ptr_list(x) for x in (g, p, m, v)]
+    hyper = dict(lr=1e-6, beta1=0.9, beta2=0.999, eps_adam=1e-8, weight_decay=1e-2)  # Table 2
+    ms, res, t_adam = [], None, 0
+    for i in range(1 + args.warmup + args.steps):
+        next_gradient(i == 0)
+        if i == 1 + args.warmup:
+            ctx.gac_profile_enable(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        res = ctx.gac_step_adamw(ptrs[0], ptrs[1], ptrs[2], ptrs[3], None, t_adam=t_adam + 1, **hyper)
+        torch.cuda.synchronize()
+        if i > args.warmup:
+            ms.append((time.perf_counter() - t0) * 1e3)
+        if res.regime != B.SKIP:
+            t_adam += 1
+    assert res.regime == B.PROJECT, (res.regime, res.c)
+    k_red, k_fin, k_app, n = ctx.gac_profile_read()
+    ms_step = sum(ms) / len(ms)
+    red_bytes, app_bytes = 4.0 * N, 30.0 * N  # bf16 g,d read; + fp32 p,m,v read and written, d written
+    out = {"metric": "fused GAC + AdamW step ms and achieved HBM GB/s", "value": (red_bytes + app_bytes) / ms_step / 1e6,
+           "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"{model.name}-style list, {len(shapes)} tensors, N={N}, bf16 g and d, fp32 m, v, p; "
+                                  "phi=0.9 consecutive gradients, thresholds (0.05, 2.0): projection regime, "
+                                  "34 bytes per element per step", "cosine": res.c, "t_adam": t_adam},
+           "roofline": {"bound": "hbm", "kernel": "apply_adamw_kernel", "achieved": app_bytes / (k_app / n) / 1e6,
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": app_bytes / (k_app / n) / 1e6 / HBM_PEAK_GBS,
+                        "traffic": None, "algorithmic_bytes_per_launch": app_bytes, "avg_launch_ms": k_app / n},
+           "kernels": {"reduce_kernel": {"avg_ms": k_red / n, "GBps": red_bytes / (k_red / n) / 1e6},
+                       "apply_adamw_kernel": {"avg_ms": k_app / n, "GBps": app_bytes / (k_app / n) / 1e6}}}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -143,6 +214,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.workload.endswith("-adamw"):
+        return main_adamw(args)
     shapes, dtype, config_id, desc = workload(args.workload)
     numel = [W.numel(s) for s in shapes]
     N = sum(numel)

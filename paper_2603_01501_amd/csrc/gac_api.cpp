@@ -73,6 +73,7 @@ struct gac_ctx {
   int chunk_elems = 0;
   int grid = 1;        // workgroups of the reduce, AdamW and state kernels (= number of partials)
   int grid_apply = 1;  // workgroups of the apply kernel
+  int grid_adamw = 1;  // workgroups of the fused AdamW apply kernel
   double c_low = 0, c_high = 0, eps = 0, beta = 1;
   int64_t step = 0;
 
@@ -275,7 +276,7 @@ int run_step(gac_ctx* ctx, void* const* grad_ptrs, bool do_reduce, const double*
   } else {
     GAC_HIP(ctx, gac::launch_apply_adamw(ctx->dtype, ctx->dev_segs, ctx->dev_adam, ctx->n_tensors,
                                          ctx->n_chunks, ctx->chunk_elems, ctx->dev_result, beta,
-                                         *adam, ctx->grid, stream));
+                                         *adam, ctx->grid_adamw, stream));
   }
   if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[3], stream));
   if (host_out != nullptr) return wait_result(ctx, host_out);
@@ -367,6 +368,7 @@ int gac_init(gac_ctx** out, const gac_config* cfg) {
   };
   ctx->grid = pick_grid(cfg->grid_blocks, gac::reduce_blocks_per_cu(ctx->dtype));
   ctx->grid_apply = pick_grid(cfg->apply_blocks, gac::apply_blocks_per_cu(ctx->dtype));
+  ctx->grid_adamw = pick_grid(cfg->apply_blocks, gac::adamw_blocks_per_cu(ctx->dtype));
 
   ctx->state.assign(n, nullptr);
   if (cfg->state_ptrs != nullptr) {

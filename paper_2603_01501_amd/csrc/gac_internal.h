@@ -54,6 +54,7 @@ enum StateOp { kStateZero = 0, kStateCopy = 1 };
 // default grids are one resident wave of workgroups (persistent kernels, static striding).
 int reduce_blocks_per_cu(int dtype);
 int apply_blocks_per_cu(int dtype);
+int adamw_blocks_per_cu(int dtype);
 
 // Launchers (defined in gac_kernels.hip).  Each validates nothing: the host side has
 // already checked shapes against the plan.  All return the launch's hipError_t.

@@ -27,6 +27,7 @@ namespace gac {
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // Pointers read from the tensor table are generic; casting them to the global address
 // space lets the compiler emit global_load/global_store instead of flat accesses.
 #define GAC_GLOBAL __attribute__((address_space(1)))
@@ -66,6 +67,15 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #endif
 #ifndef GAC_APPLY_NT_STORE
 #define GAC_APPLY_NT_STORE 1
+#endif
+#ifndef GAC_ADAMW_THREADS
+#define GAC_ADAMW_THREADS 256
+#endif
+#ifndef GAC_ADAMW_NT_LOAD
+#define GAC_ADAMW_NT_LOAD 1
+#endif
+#ifndef GAC_ADAMW_QUADS
+#define GAC_ADAMW_QUADS 2
 #endif
 
 template <int DT> struct Elem;
@@ -546,13 +556,125 @@ __device__ __forceinline__ void adamw_elem(float g, float& p, float& m, float& v
   p = p - h.step_size * m / (sqrtf(v) * h.inv_sqrt_bc2 + h.eps_adam);
 }
 
+// Four consecutive gradient elements as stored: 16 bytes of fp32 or 8 bytes of bf16.
+template <int DT> struct Quad;
+template <> struct Quad<GAC_F32> {
+  typedef u32x4 type;
+};
+template <> struct Quad<GAC_BF16> {
+  typedef u32x2 type;
+};
+
 template <int DT>
-__global__ __launch_bounds__(kThreads) void apply_adamw_kernel(
+__device__ __forceinline__ void unpack_quad(typename Quad<DT>::type q, float (&x)[4]) {
+  if constexpr (DT == GAC_F32) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x[i] = __uint_as_float(q[i]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      x[2 * i] = __uint_as_float(q[i] << 16);
+      x[2 * i + 1] = __uint_as_float(q[i] & 0xffff0000u);
+    }
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ typename Quad<DT>::type pack_quad(const float (&x)[4]) {
+  typename Quad<DT>::type q;
+  if constexpr (DT == GAC_F32) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) q[i] = __float_as_uint(x[i]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) q[i] = pack_bf16x2(x[2 * i], x[2 * i + 1]);
+  }
+  return q;
+}
+
+// The fused pass works in quads (4 elements): lane l of a workgroup takes quads l, l+T, ...
+// so that every load and store instruction of a wave covers one contiguous range, both for
+// the 2-byte gradient / state (8 bytes per lane) and for the 4-byte optimizer state (16 bytes
+// per lane).  Q quads per lane are in flight at a time.
+template <int DT, int Q, int NTL>
+__device__ __forceinline__ void adamw_quads(const gchar* ga, gchar* gb, gfloat* pp, gfloat* pm,
+                                            gfloat* pv, gchar* pl, int j0, int stride,
+                                            bool project, bool skip, float k, float beta,
+                                            const AdamScalars& h) {
+  typedef typename Quad<DT>::type quad_t;
+  typedef GAC_GLOBAL quad_t gquad;
+  const gquad* gq = reinterpret_cast<const gquad*>(ga);
+  gquad* dq = reinterpret_cast<gquad*>(gb);
+  gvec* vp = reinterpret_cast<gvec*>(pp);
+  gvec* vm = reinterpret_cast<gvec*>(pm);
+  gvec* vv = reinterpret_cast<gvec*>(pv);
+  gquad* lq = reinterpret_cast<gquad*>(pl);
+  quad_t a[Q];
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    if constexpr (NTL) {
+      a[q] = __builtin_nontemporal_load(gq + j0 + q * stride);
+    } else {
+      a[q] = gq[j0 + q * stride];
+    }
+  }
+  if (skip) {  // violation: only the reference state moves, the optimizer is untouched
+#pragma unroll
+    for (int q = 0; q < Q; ++q) __builtin_nontemporal_store(a[q], dq + j0 + q * stride);
+    return;
+  }
+  quad_t b[Q];
+  if (project) {
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+      if constexpr (NTL) {
+        b[q] = __builtin_nontemporal_load(dq + j0 + q * stride);
+      } else {
+        b[q] = dq[j0 + q * stride];
+      }
+    }
+  }
+  u32x4 P[Q], M[Q], V[Q];
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    P[q] = ld16<NTL>(vp + j0 + q * stride);
+    M[q] = ld16<NTL>(vm + j0 + q * stride);
+    V[q] = ld16<NTL>(vv + j0 + q * stride);
+  }
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    float x[4];
+    unpack_quad<DT>(a[q], x);
+    if (project) {
+      float y[4];
+      unpack_quad<DT>(b[q], y);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[e] = fmaf(k, y[e], beta * x[e]);
+    }
+    float pnew[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float p = __uint_as_float(P[q][e]), m = __uint_as_float(M[q][e]), v = __uint_as_float(V[q][e]);
+      adamw_elem(x[e], p, m, v, h);
+      P[q][e] = __float_as_uint(p);
+      M[q][e] = __float_as_uint(m);
+      V[q][e] = __float_as_uint(v);
+      pnew[e] = p;
+    }
+    st16<1>(vp + j0 + q * stride, P[q]);
+    st16<1>(vm + j0 + q * stride, M[q]);
+    st16<1>(vv + j0 + q * stride, V[q]);
+    __builtin_nontemporal_store(a[q], dq + j0 + q * stride);
+    if (pl != nullptr) __builtin_nontemporal_store(pack_quad<DT>(pnew), lq + j0 + q * stride);
+  }
+}
+
+template <int DT, int T>
+__global__ __launch_bounds__(T) void apply_adamw_kernel(
     const Seg* __restrict__ segs, const AdamSeg* __restrict__ adam, int n_tensors,
     int64_t n_chunks, int chunk_elems, const gac_result* __restrict__ res, float beta,
     AdamScalars h) {
-  constexpr int N = Elem<DT>::kPerVec;
-  constexpr int R = N / 4;  // 16-byte vectors of fp32 optimizer state per gradient vector
+  constexpr int Q = GAC_ADAMW_QUADS;
   if (res->nonfinite) return;
   const int regime = res->regime;
   const bool project = regime == GAC_PROJECT;
@@ -571,60 +693,15 @@ __global__ __launch_bounds__(kThreads) void apply_adamw_kernel(
                         aligned16(pv) && aligned16(pl);
     int first_scalar = 0;
     if (vec_ok) {
-      const gvec* gv = reinterpret_cast<const gvec*>(ch.a);
-      gvec* dv = reinterpret_cast<gvec*>(ch.b);
-      gvec* vp = reinterpret_cast<gvec*>(pp);
-      gvec* vm = reinterpret_cast<gvec*>(pm);
-      gvec* vv = reinterpret_cast<gvec*>(pv);
-      gvec* vl = reinterpret_cast<gvec*>(pl);
-      const int nvec = ch.len / N;
-      for (int i = tid; i < nvec; i += kThreads) {
-        const u32x4 a = ld16(gv + i);
-        if (skip) {  // violation: only the reference state moves, the optimizer is untouched
-          st16(dv + i, a);
-          continue;
-        }
-        float x[N];
-        unpack<DT>(a, x);
-        if (project) {
-          float y[N];
-          unpack<DT>(ld16(dv + i), y);
-#pragma unroll
-          for (int e = 0; e < N; ++e) x[e] = fmaf(k, y[e], beta * x[e]);
-        }
-        u32x4 P[R], M[R], V[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-          P[r] = ld16(vp + i * R + r);
-          M[r] = ld16(vm + i * R + r);
-          V[r] = ld16(vv + i * R + r);
-        }
-        float pnew[N];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            float p = __uint_as_float(P[r][q]), m = __uint_as_float(M[r][q]),
-                  v = __uint_as_float(V[r][q]);
-            adamw_elem(x[4 * r + q], p, m, v, h);
-            P[r][q] = __float_as_uint(p);
-            M[r][q] = __float_as_uint(m);
-            V[r][q] = __float_as_uint(v);
-            pnew[4 * r + q] = p;
-          }
-        }
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-          st16(vp + i * R + r, P[r]);
-          st16(vm + i * R + r, M[r]);
-          st16(vv + i * R + r, V[r]);
-        }
-        st16(dv + i, a);
-        if (pl != nullptr) st16(vl + i, pack<DT>(pnew));
-      }
-      first_scalar = nvec * N;
+      const int nquad = ch.len / 4;
+      int j = tid;
+      for (; j + (Q - 1) * T < nquad; j += Q * T)
+        adamw_quads<DT, Q, GAC_ADAMW_NT_LOAD>(ch.a, ch.b, pp, pm, pv, pl, j, T, project, skip, k, beta, h);
+      for (; j < nquad; j += T)
+        adamw_quads<DT, 1, GAC_ADAMW_NT_LOAD>(ch.a, ch.b, pp, pm, pv, pl, j, T, project, skip, k, beta, h);
+      first_scalar = nquad * 4;
     }
-    for (int i = first_scalar + tid; i < ch.len; i += kThreads) {
+    for (int i = first_scalar + tid; i < ch.len; i += T) {
       if (!skip) {
         float g = load_elem<DT>(ch.a, i);
         if (project) g = fmaf(k, load_elem<DT>(ch.b, i), beta * g);
@@ -689,6 +766,16 @@ int reduce_blocks_per_cu(int dtype) {
   return (e == hipSuccess && n > 0) ? n : 1;
 }
 
+int adamw_blocks_per_cu(int dtype) {
+  int n = 0;
+  hipError_t e = dtype == GAC_F32
+      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(
+            &n, apply_adamw_kernel<GAC_F32, GAC_ADAMW_THREADS>, GAC_ADAMW_THREADS, 0)
+      : hipOccupancyMaxActiveBlocksPerMultiprocessor(
+            &n, apply_adamw_kernel<GAC_BF16, GAC_ADAMW_THREADS>, GAC_ADAMW_THREADS, 0);
+  return (e == hipSuccess && n > 0) ? n : 1;
+}
+
 int apply_blocks_per_cu(int dtype) {
   int n = 0;
   hipError_t e = dtype == GAC_F32
@@ -739,10 +826,10 @@ hipError_t launch_apply_adamw(int dtype, const Seg* dev_segs, const AdamSeg* dev
                               const gac_result* dev_result, float beta, AdamScalars h, int grid,
                               hipStream_t stream) {
   if (dtype == GAC_F32) {
-    apply_adamw_kernel<GAC_F32><<<grid, kThreads, 0, stream>>>(
+    apply_adamw_kernel<GAC_F32, GAC_ADAMW_THREADS><<<grid, GAC_ADAMW_THREADS, 0, stream>>>(
         dev_segs, dev_adam, n_tensors, n_chunks, chunk_elems, dev_result, beta, h);
   } else {
-    apply_adamw_kernel<GAC_BF16><<<grid, kThreads, 0, stream>>>(
+    apply_adamw_kernel<GAC_BF16, GAC_ADAMW_THREADS><<<grid, GAC_ADAMW_THREADS, 0, stream>>>(
         dev_segs, dev_adam, n_tensors, n_chunks, chunk_elems, dev_result, beta, h);
   }
   return hipGetLastError();
