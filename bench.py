@@ -247,9 +247,34 @@ def main():
     step_bytes = 6.0 * N * es
     value = step_bytes / (ms_step * 1e-3) / 1e9
 
+    def run_exchange(c_high, warmup, steps):
+        """The same steps through gac_step_exchange: buffers change hands, no snapshot copy."""
+        state = [torch.zeros(s, dtype=dtype, device="cuda:0") for s in shapes]
+        ctx = B.Gac(numel, code, c_low=0.05, c_high=c_high, state=state, chunk_elems=args.chunk_elems,
+                    grid_blocks=args.grid_blocks, apply_blocks=args.apply_blocks)
+        mine, ms, res = g, [], None
+        for i in range(1 + warmup + steps):
+            stream.next_into(mine)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            res, mine = ctx.gac_step_exchange(mine)
+            torch.cuda.synchronize()
+            if i > warmup:
+                ms.append((time.perf_counter() - t0) * 1e3)
+        ctx.close()
+        del state, mine
+        torch.cuda.empty_cache()
+        return ms, res
+
     ms_d, res_d, (d_red, d_fin, d_app) = run(0.3, 1, max(3, min(5, args.steps)))
     assert res_d.regime == B.SKIP
     ms_step_d = sum(ms_d) / len(ms_d)
+
+    n_x = max(3, min(8, args.steps))
+    ms_xp, res_xp = run_exchange(2.0, 1, n_x)
+    g = [torch.empty(s, dtype=dtype, device="cuda:0") for s in shapes]  # the old ones changed hands
+    ms_xs, res_xs = run_exchange(0.3, 1, n_x)
+    assert res_xp.regime == B.PROJECT and res_xs.regime == B.SKIP
 
     sha = hashlib.sha256(open(gac_build.SOURCES[0], "rb").read()).hexdigest()
     apply_bytes = 4.0 * N * es
@@ -278,6 +303,13 @@ def main():
                                      "bytes_per_step": 4.0 * N * es,
                                      "GBps": 4.0 * N * es / (ms_step_d * 1e-3) / 1e9,
                                      "reduce_ms": d_red, "apply_copy_ms": d_app},
+        "exchange_form": {"what": "gac_step_exchange: the gradient buffers become the reference state and "
+                                  "the old state buffers come back (holding g' when projected)",
+                          "projection": {"ms_per_step": sum(ms_xp) / len(ms_xp), "bytes_per_step": 5.0 * N * es,
+                                         "GBps": 5.0 * N * es / (sum(ms_xp) / len(ms_xp)) / 1e6},
+                          "paper_default_thresholds_skip": {"ms_per_step": sum(ms_xs) / len(ms_xs),
+                                                            "bytes_per_step": 2.0 * N * es,
+                                                            "GBps": 2.0 * N * es / (sum(ms_xs) / len(ms_xs)) / 1e6}},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shapes, dtype, torch)

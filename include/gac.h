@@ -122,6 +122,22 @@ void gac_destroy(gac_ctx* ctx);
  * host_out was given (otherwise GAC_OK, and the flag is in the device result). */
 int gac_step(gac_ctx* ctx, void* const* grad_ptrs, void* hip_stream, gac_result* host_out);
 
+/* The same update without the snapshot copy, for callers that can let buffers change hands.
+ * Requires a context whose state buffers were provided by the caller (cfg->state_ptrs) and
+ * host_out != NULL.  The g buffers passed in BECOME the reference state (the raw gradient is
+ * the next reference: Algorithm 1, Appendix A.2) and the buffers that held the previous
+ * reference state are returned in grad_ptrs:
+ *   GAC_PROJECT  the returned buffers hold the projected gradient g' (Eq. 4): give those to
+ *                the optimizer.  Traffic: 2 N s (statistics) + 3 N s instead of 6 N s.
+ *   GAC_SAFE     the gradient to use is still in the buffers that were passed in; they now
+ *                belong to the library and must only be read.  GAC_SKIP: no update.
+ *                Nothing is moved at all (2 N s for the statistics only); the content of the
+ *                returned buffers is unspecified.
+ * In every regime the returned buffers are free for the caller's next gradient once the
+ * optimizer is done with them.  On GAC_ERR_NONFINITE no buffer changes hands.  The call
+ * returns when the regime is known; pass 2 may still be running on the stream. */
+int gac_step_exchange(gac_ctx* ctx, void** grad_ptrs, void* hip_stream, gac_result* host_out);
+
 /* Data-parallel form of the same update (Appendix A.1: each rank reduces its shard, one
  * all-reduce of three scalars, then each rank applies).  Phase 1 writes the rank-local
  * {<g,d>, <g,g>, <d,d>} to dev_sums3 (device, 3 doubles).  The caller sums them across

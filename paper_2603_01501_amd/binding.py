@@ -82,6 +82,7 @@ def lib() -> ctypes.CDLL:
         "gac_init": (ctypes.c_int, [ctypes.POINTER(vp), ctypes.POINTER(GacConfig)]),
         "gac_destroy": (None, [vp]),
         "gac_step": (ctypes.c_int, [vp, vpp, vp, resp]),
+        "gac_step_exchange": (ctypes.c_int, [vp, vpp, vp, resp]),
         "gac_reduce_local": (ctypes.c_int, [vp, vpp, vp, vp]),
         "gac_apply": (ctypes.c_int, [vp, vpp, vp, vp, resp]),
         "gac_step_adamw": (ctypes.c_int, [vp, vpp, vpp, vpp, vpp, vpp, ctypes.POINTER(GacAdamWHyper), vp, resp]),
@@ -191,6 +192,22 @@ class Gac:
                             ctypes.byref(res) if sync else None)
         self._check(rc)
         return res
+
+    def gac_step_exchange(self, grads: Sequence, stream=None):
+        """Returns (result, returned): ``returned`` are the tensors that held the reference
+        state before the call (holding g' in the projection regime); ``grads`` now belong to
+        the library as the new reference state.  Tensors are tracked by device pointer."""
+        ptrs = ptr_list(list(grads))
+        by_ptr = {t.data_ptr(): t for t in self._state_keepalive}
+        res = GacResult()
+        rc = lib().gac_step_exchange(self._ctx, ptrs, _stream_handle(stream), ctypes.byref(res))
+        self._check(rc)
+        if rc == ERR_NONFINITE:
+            return res, list(grads)
+        returned = [by_ptr[ptrs[j]] if ptrs[j] is not None else self._state_keepalive[j]
+                    for j in range(len(grads))]
+        self._state_keepalive = list(grads)
+        return res, returned
 
     def gac_reduce_local(self, grads: Sequence, dev_sums3, stream=None) -> None:
         rc = lib().gac_reduce_local(self._ctx, ptr_list(grads), _stream_handle(stream),

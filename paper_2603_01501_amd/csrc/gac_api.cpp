@@ -79,6 +79,7 @@ struct gac_ctx {
 
   std::vector<void*> state;    // device pointers of d, one per tensor
   void* state_alloc = nullptr; // owned allocation backing `state`, or null
+  bool state_is_callers = false;  // the state buffers were provided by the caller
 
   // pointer tables
   Seg* dev_segs = nullptr;
@@ -245,7 +246,7 @@ int state_op(gac_ctx* ctx, int op, const void* const* src, void* const* dst, hip
 }
 
 // Steps shared by gac_step / gac_apply / gac_step_adamw after the sums are available.
-enum class ApplyKind { kPlain, kAdamW };
+enum class ApplyKind { kPlain, kAdamW, kExchange };
 
 int run_step(gac_ctx* ctx, void* const* grad_ptrs, bool do_reduce, const double* sums_in,
              ApplyKind kind, const AdamScalars* adam, hipStream_t stream, gac_result* host_out) {
@@ -270,7 +271,10 @@ int run_step(gac_ctx* ctx, void* const* grad_ptrs, bool do_reduce, const double*
   }
   if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[2], stream));
   const float beta = static_cast<float>(ctx->beta);
-  if (kind == ApplyKind::kPlain) {
+  if (kind == ApplyKind::kExchange) {
+    GAC_HIP(ctx, gac::launch_exchange(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
+                                      ctx->chunk_elems, ctx->dev_result, beta, ctx->grid_apply, stream));
+  } else if (kind == ApplyKind::kPlain) {
     GAC_HIP(ctx, gac::launch_apply(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
                                    ctx->chunk_elems, ctx->dev_result, beta, ctx->grid_apply, stream));
   } else {
@@ -373,6 +377,7 @@ int gac_init(gac_ctx** out, const gac_config* cfg) {
   ctx->state.assign(n, nullptr);
   if (cfg->state_ptrs != nullptr) {
     for (int j = 0; j < n; ++j) ctx->state[j] = cfg->state_ptrs[j];
+    ctx->state_is_callers = true;
   } else {
     // one allocation, every tensor's slice 256-byte aligned
     const int64_t es = elem_size(ctx->dtype);
@@ -454,6 +459,24 @@ int gac_step(gac_ctx* ctx, void* const* grad_ptrs, void* hip_stream, gac_result*
   DeviceGuard guard(ctx->device);
   return run_step(ctx, grad_ptrs, true, nullptr, ApplyKind::kPlain, nullptr,
                   static_cast<hipStream_t>(hip_stream), host_out);
+}
+
+int gac_step_exchange(gac_ctx* ctx, void** grad_ptrs, void* hip_stream, gac_result* host_out) {
+  if (ctx == nullptr || host_out == nullptr || !ctx->state_is_callers) return GAC_ERR_INVALID_ARG;
+  int rc = check_ptrs(ctx, const_cast<const void* const*>(grad_ptrs));
+  if (rc != GAC_OK) return rc;
+  for (int j = 0; j < ctx->n_tensors; ++j)
+    if (ctx->numel[j] > 0 && grad_ptrs[j] == ctx->state[j]) return GAC_ERR_INVALID_ARG;
+  DeviceGuard guard(ctx->device);
+  rc = run_step(ctx, grad_ptrs, true, nullptr, ApplyKind::kExchange, nullptr,
+                static_cast<hipStream_t>(hip_stream), host_out);
+  if (rc != GAC_OK) return rc;  // includes the non-finite case: no buffer changes hands
+  for (int j = 0; j < ctx->n_tensors; ++j) {
+    void* old_state = ctx->state[j];
+    ctx->state[j] = grad_ptrs[j];
+    grad_ptrs[j] = old_state;
+  }
+  return GAC_OK;
 }
 
 int gac_reduce_local(gac_ctx* ctx, void* const* grad_ptrs, void* hip_stream, double* dev_sums3) {

@@ -71,6 +71,11 @@ hipError_t launch_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n
                         int chunk_elems, const gac_result* dev_result, float beta, int grid,
                         hipStream_t stream);
 
+// Buffer-exchange pass 2: writes g' over the old state (Seg::b) in the projection regime only.
+hipError_t launch_exchange(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
+                           int chunk_elems, const gac_result* dev_result, float beta, int grid,
+                           hipStream_t stream);
+
 hipError_t launch_apply_adamw(int dtype, const Seg* dev_segs, const AdamSeg* dev_adam,
                               int n_tensors, int64_t n_chunks, int chunk_elems,
                               const gac_result* dev_result, float beta, AdamScalars h, int grid,

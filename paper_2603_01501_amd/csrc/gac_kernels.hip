@@ -543,6 +543,86 @@ __global__ __launch_bounds__(T) void apply_kernel(const Seg* __restrict__ segs,
   }
 }
 
+// Pass 2 of the buffer-exchange form: the projected gradient is written over the OLD
+// reference state (which nobody needs after this step) and g itself is left alone, because
+// the caller hands the g buffers over as the new reference state.  Projection regime:
+// read g, read d, write g' (3 N s bytes); in the other regimes there is nothing to move.
+template <int DT, int T, int U>
+__global__ __launch_bounds__(T) void exchange_kernel(const Seg* __restrict__ segs,
+                                                            int n_tensors, int64_t n_chunks,
+                                                            int chunk_elems,
+                                                            const gac_result* __restrict__ res,
+                                                            float beta) {
+  constexpr int N = Elem<DT>::kPerVec;
+  if (res->nonfinite || res->regime != GAC_PROJECT) return;
+  const float k = static_cast<float>(res->coef);
+  const int tid = threadIdx.x;
+
+  struct Tile {
+    u32x4 a[U], b[U];
+  };
+  auto whole = [&](const Chunk& ch) {
+    return ch.len == T * U * N && aligned16(ch.a) && aligned16(ch.b);
+  };
+  auto load_tile = [&](const Chunk& ch, Tile& tl) {
+    const gvec* gv = reinterpret_cast<const gvec*>(ch.a) + tid;
+    const gvec* dv = reinterpret_cast<const gvec*>(ch.b) + tid;
+#pragma unroll
+    for (int u = 0; u < U; ++u) tl.a[u] = ld16<GAC_APPLY_NT_LOAD>(gv + u * T);
+#pragma unroll
+    for (int u = 0; u < U; ++u) tl.b[u] = ld16<GAC_APPLY_NT_LOAD>(dv + u * T);
+  };
+  auto store_tile = [&](const Chunk& ch, const Tile& tl) {
+    gvec* dv = reinterpret_cast<gvec*>(ch.b) + tid;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      st16<GAC_APPLY_NT_STORE>(dv + u * T, project_vec<DT>(tl.a[u], tl.b[u], k, beta));
+  };
+  auto generic = [&](const Chunk& ch) {
+    int first_scalar = 0;
+    if (aligned16(ch.a) && aligned16(ch.b)) {
+      const gvec* gv = reinterpret_cast<const gvec*>(ch.a);
+      gvec* dv = reinterpret_cast<gvec*>(ch.b);
+      const int nvec = ch.len / N;
+      for (int i = tid; i < nvec; i += T)
+        st16<GAC_APPLY_NT_STORE>(dv + i, project_vec<DT>(ld16<GAC_APPLY_NT_LOAD>(gv + i),
+                                                         ld16<GAC_APPLY_NT_LOAD>(dv + i), k, beta));
+      first_scalar = nvec * N;
+    }
+    for (int i = first_scalar + tid; i < ch.len; i += T)
+      store_elem<DT>(ch.b, i, fmaf(k, load_elem<DT>(ch.b, i), beta * load_elem<DT>(ch.a, i)));
+  };
+
+  int t = n_tensors - 1;
+  int64_t cr = blockIdx.x;
+  if (cr >= n_chunks) return;
+  Chunk cur = locate<true>(segs, t, n_chunks - 1 - cr, chunk_elems, Elem<DT>::kSize);
+  bool cur_whole = whole(cur);
+  Tile tc = {};
+  if (cur_whole) load_tile(cur, tc);
+  for (;;) {
+    cr += gridDim.x;
+    const bool more = cr < n_chunks;
+    Chunk next = cur;
+    bool next_whole = false;
+    Tile tn = {};
+    if (more) {
+      next = locate<true>(segs, t, n_chunks - 1 - cr, chunk_elems, Elem<DT>::kSize);
+      next_whole = whole(next);
+      if (next_whole) load_tile(next, tn);
+    }
+    if (cur_whole) {
+      store_tile(cur, tc);
+    } else {
+      generic(cur);
+    }
+    if (!more) break;
+    cur = next;
+    cur_whole = next_whole;
+    tc = tn;
+  }
+}
+
 // ------------------------------------------------------------------ pass 2 fused with AdamW
 
 // One AdamW update of one element (decoupled weight decay), fp32, in the operation order
@@ -816,6 +896,19 @@ hipError_t launch_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n
         dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, beta);
   } else {
     apply_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, beta);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_exchange(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
+                           int chunk_elems, const gac_result* dev_result, float beta, int grid,
+                           hipStream_t stream) {
+  if (dtype == GAC_F32) {
+    exchange_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, beta);
+  } else {
+    exchange_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
         dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, beta);
   }
   return hipGetLastError();

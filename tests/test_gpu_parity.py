@@ -329,3 +329,63 @@ def test_pointer_list_may_change_between_steps():
           zip(g1, d, make(shapes, torch.float32, 0.0, config_id=21)[0])]
     assert g2[0].data_ptr() != g1[0].data_ptr()
     step_and_check(ctx, g2, d, torch.float32)
+
+
+# ------------------------------------------------------------------ buffer-exchange form
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_exchange_form_matches_in_place_form_over_consecutive_steps(dtype):
+    """gac_step_exchange hands buffers back and forth instead of copying the snapshot; its
+    statistics, regimes, projected gradients and state must equal gac_step's bit for bit, and
+    the in-place form is itself checked against the oracle here."""
+    model = W.scaled_down(W.MODEL_76B, 28, layers=1, vocab=2001)
+    shapes = model.tensor_shapes() + [(5,), (0,), (2049,)]
+    numel = [W.numel(s) for s in shapes]
+    stream_a = W.AR1Stream(shapes, dtype, 0.3, 1e-3, config_id=23, device=DEV)
+    thresholds = [(C_LOW, C_HIGH)] * 2 + [(C_LOW, 0.9), (0.5, 0.9), (0.01, 0.2), (C_LOW, 0.9)]
+    ref = new_ctx(shapes, dtype)                       # in-place form, library-owned state
+    bufs = [torch.zeros(s, dtype=dtype, device=DEV) for s in shapes]
+    ex = new_ctx(shapes, dtype, state=bufs)            # exchange form, caller-owned state
+    mine = [torch.empty(s, dtype=dtype, device=DEV) for s in shapes]
+    seen = set()
+    for t, (lo, hi) in enumerate(thresholds, start=1):
+        g = stream_a.next()
+        for a, b in zip(mine, g):
+            a.copy_(b)
+        g_raw = U.clone_list(g)
+        d_before = ctx_state(ref, g)
+        ref.gac_set_thresholds(lo, hi)
+        ex.gac_set_thresholds(lo, hi)
+        r1 = ref.gac_step(g)
+        passed = mine
+        r2, returned = ex.gac_step_exchange(passed)
+        torch.cuda.synchronize()
+        U.check_step(r1, g_raw, d_before, g, ctx_state(ref, g), dtype, lo, hi, EPS)
+        assert (r2.dot, r2.gg, r2.dd, r2.c, r2.coef, r2.regime, r2.step) == \
+               (r1.dot, r1.gg, r1.dd, r1.c, r1.coef, r1.regime, r1.step)
+        seen.add(r2.regime)
+        # the buffers that were passed in are untouched and are now the reference state
+        assert all(U.bits_equal(a, b) for a, b in zip(passed, g_raw))
+        assert all(U.bits_equal(a, b) for a, b in zip(ctx_state(ex, g), g_raw))
+        assert all(a.data_ptr() != b.data_ptr() for a, b, n in zip(passed, returned, numel) if n)
+        if r2.regime == B.PROJECT:
+            assert all(U.bits_equal(a, b) for a, b in zip(returned, g)), "returned buffers must hold g'"
+        mine = returned  # free for the next gradient
+    assert seen == {B.SAFE, B.PROJECT, B.SKIP}
+
+
+def test_exchange_form_argument_checks():
+    shapes = [(4096,)]
+    g, d = make(shapes, torch.float32, 0.15, config_id=24)
+    ctx = new_ctx(shapes, torch.float32)  # library-owned state: nothing to hand over
+    res = B.GacResult()
+    arr = B.ptr_list(g)
+    assert B.lib().gac_step_exchange(ctx._ctx, arr, None, ctypes.byref(res)) == B.ERR_INVALID_ARG
+    ctx2 = new_ctx(shapes, torch.float32, state=d)
+    assert B.lib().gac_step_exchange(ctx2._ctx, arr, None, None) == B.ERR_INVALID_ARG
+    same = B.ptr_list(d)
+    assert B.lib().gac_step_exchange(ctx2._ctx, same, None, ctypes.byref(res)) == B.ERR_INVALID_ARG
+    g[0][5] = float("nan")
+    before = arr[0]
+    assert B.lib().gac_step_exchange(ctx2._ctx, arr, None, ctypes.byref(res)) == B.ERR_NONFINITE
+    assert arr[0] == before and res.nonfinite == 1  # no buffer changed hands
