@@ -532,7 +532,7 @@ int gac_step_adamw(gac_ctx* ctx, void* const* grad_ptrs, float* const* master_p,
   h.one_minus_beta1 = static_cast<float>(1.0 - hyper->beta1);
   h.beta2 = static_cast<float>(hyper->beta2);
   h.one_minus_beta2 = static_cast<float>(1.0 - hyper->beta2);
-  h.decay = static_cast<float>(1.0 - hyper->lr * hyper->weight_decay);
+  h.lr_wd = static_cast<float>(hyper->lr * hyper->weight_decay);
   h.step_size = static_cast<float>(hyper->lr / bc1);
   h.inv_sqrt_bc2 = static_cast<float>(1.0 / std::sqrt(bc2));
   h.eps_adam = static_cast<float>(hyper->eps_adam);

@@ -39,7 +39,7 @@ struct DecideParams {
 struct AdamScalars {
   float beta1, one_minus_beta1;
   float beta2, one_minus_beta2;
-  float decay;         // 1 - lr * weight_decay
+  float lr_wd;         // lr * weight_decay
   float step_size;     // lr / (1 - beta1^t)
   float inv_sqrt_bc2;  // 1 / sqrt(1 - beta2^t)
   float eps_adam;

@@ -625,15 +625,18 @@ __global__ __launch_bounds__(T) void exchange_kernel(const Seg* __restrict__ seg
 
 // ------------------------------------------------------------------ pass 2 fused with AdamW
 
-// One AdamW update of one element (decoupled weight decay), fp32, in the operation order
-//   m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;  p <- p (1 - lr wd);
-//   p <- p - (lr/(1-b1^t)) m / (sqrt(v)/sqrt(1-b2^t) + eps)
+// One AdamW update of one element (decoupled weight decay) in fp32:
+//   m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
+//   p <- p - [ lr wd p + (lr/(1-b1^t)) m / (sqrt(v)/sqrt(1-b2^t) + eps) ]
+// The decay term and the Adam step are added before they are subtracted from p, so p is
+// rounded once; with lr wd far below one ulp (1e-8 at the paper's settings) a separate
+// p (1 - lr wd) would round to p and lose the decay altogether.
 __device__ __forceinline__ void adamw_elem(float g, float& p, float& m, float& v,
                                            const AdamScalars& h) {
   m = fmaf(h.beta1, m, h.one_minus_beta1 * g);
   v = fmaf(h.beta2, v, h.one_minus_beta2 * (g * g));
-  p = p * h.decay;
-  p = p - h.step_size * m / (sqrtf(v) * h.inv_sqrt_bc2 + h.eps_adam);
+  const float step = h.step_size * m / (sqrtf(v) * h.inv_sqrt_bc2 + h.eps_adam);
+  p = p - fmaf(h.lr_wd, p, step);
 }
 
 // Four consecutive gradient elements as stored: 16 bytes of fp32 or 8 bytes of bf16.

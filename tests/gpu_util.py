@@ -78,3 +78,15 @@ def check_step(res, g_before: Sequence[torch.Tensor], d_before: Sequence[torch.T
 
 def clone_list(ts: Sequence[torch.Tensor]) -> List[torch.Tensor]:
     return [t.clone() for t in ts]
+
+
+def adamw_param_tolerance(p_old: np.ndarray, m_old: np.ndarray, v_new: np.ndarray, g: np.ndarray,
+                          lr: float, beta1: float, beta2: float, eps_adam: float, t: int) -> np.ndarray:
+    """Element-wise bound for an fp32 AdamW parameter against the fp64 oracle: two roundings of
+    the parameter (2 ulp) plus 1e-5 of the step evaluated with |m| and |g| - the first moment
+    b1 m + (1-b1) g can cancel, and then the fp32 rounding of its two terms, not the size of
+    the step itself, sets the error."""
+    bc1, bc2 = 1.0 - beta1 ** t, 1.0 - beta2 ** t
+    step_abs = lr * (beta1 * np.abs(m_old.astype(np.float64)) + (1.0 - beta1) * np.abs(g)) / bc1 / \
+        (np.sqrt(v_new / bc2) + eps_adam)
+    return 2.0 * np.spacing(np.abs(p_old)).astype(np.float64) + 1e-5 * step_abs

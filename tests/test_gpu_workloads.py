@@ -163,3 +163,106 @@ def test_seven_billion_bf16_list_consecutive_steps():
     torch.cuda.synchronize()
     assert all(U.bits_equal(a, b) for a, b in zip(state, g3))
     ctx.close()
+
+
+def test_single_tensor_beyond_two_to_the_31_elements():
+    """One bf16 tensor of 2^31 + 4099 elements (plus a small neighbour): element offsets inside
+    a tensor need 64 bits; the tail chunk is ragged and not a multiple of the vector width."""
+    dtype = torch.bfloat16
+    n_big = (1 << 31) + 4099
+    shapes = [(7,), (n_big,), (33,)]
+    g, d0 = [], []
+    for j, s in enumerate(shapes):
+        gen = torch.Generator(device=DEV)
+        gen.manual_seed(W.tensor_seed(8, j))
+        dd = torch.randn(s, generator=gen, device=DEV, dtype=dtype)
+        gg = torch.randn(s, generator=gen, device=DEV, dtype=dtype).mul_(0.98).add_(dd, alpha=0.2)
+        g.append(gg)
+        d0.append(dd)
+    d = U.clone_list(d0)
+    ctx = B.Gac([W.numel(s) for s in shapes], B.BF16, state=d)
+    ctx.gac_state_import(d0, 0)
+    g_raw = U.clone_list(g)
+    res = ctx.gac_step(g)
+    torch.cuda.synchronize()
+    g_h, d_h, s, dec = oracle_decision(g_raw, d0, dtype, C_LOW, C_HIGH)
+    check_result(res, s, dec)
+    assert res.regime == B.PROJECT
+    assert all(U.bits_equal(a, b) for a, b in zip(d, g_raw))
+    # the projected gradient: small tensors whole, the big one on its first and last 2^20 elements
+    dt = B.BF16
+    k = (dec.alpha - 1.0) * s[0] / s[2]
+    for j in (0, 2):
+        want = O.project_decomposed(g_h[j], d_h[j], dt, s, dec.alpha)
+        assert U.rel_l2([g[j]], [want]) <= U.GRAD_TOL[dt]
+    m = 1 << 20
+    for sl in (slice(0, m), slice(n_big - m, n_big), slice((1 << 31) - m // 2, (1 << 31) + m // 2)):
+        want = O.project_rank_one(np.ascontiguousarray(g_h[1][sl]), np.ascontiguousarray(d_h[1][sl]), dt, s, dec.alpha)
+        assert U.rel_l2([g[1][sl]], [want]) <= U.GRAD_TOL[dt]
+    say(f"  c={res.c:.6f} coef={res.coef:.6f} (oracle k={k:.6f})")
+    ctx.close()
+
+
+def test_fourteen_billion_list_fused_adamw_full_shape():
+    """14B-style list (435 tensors, 14,769,689,600 elements): bf16 g and d, fp32 m, v and master
+    parameters, rho = 0.9, thresholds (0.05, 2.0): projection fused with AdamW in one pass.
+    Statistics against the oracle over all elements; optimizer state against the unfused
+    oracle composition on sampled tensors (embedding slice, one layer, final norm); g is
+    untouched and the state equals the raw gradient bitwise, checked on the GPU."""
+    dtype = torch.bfloat16
+    shapes = W.MODEL_14B.tensor_shapes()
+    numel = [W.numel(s) for s in shapes]
+    say("generating")
+    g, d = W.correlated_pair(shapes, dtype, 0.9, 1e-3, config_id=5, device=DEV)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(777)
+    p = [torch.randn(s, generator=gen, device=DEV).mul_(0.02) for s in shapes]
+    m = [torch.randn(s, generator=gen, device=DEV).mul_(1e-4) for s in shapes]
+    v = [torch.rand(s, generator=gen, device=DEV).mul_(1e-6) for s in shapes]
+    sample = [2, 3, 4, 5, 6, 7, 8, 9, 10, len(shapes) - 1]      # first layer's 9 tensors, final norm
+    emb_rows = slice(0, 4096)                                    # a slice of the embedding
+    keep = {j: (W.to_oracle_array(p[j]), W.to_oracle_array(m[j]), W.to_oracle_array(v[j])) for j in sample}
+    keep_emb = tuple(W.to_oracle_array(t[0][emb_rows]) for t in (p, m, v))
+    say("oracle sums over all elements")
+    g_h, d_h, s, dec = oracle_decision(g, d, dtype, C_LOW, 2.0)
+    d_h = {j: d_h[j] for j in sample + [0]}
+    g_h = {j: g_h[j] for j in sample + [0]}
+    d0_emb = d[0][emb_rows].clone()
+    state = d
+    ctx = B.Gac(numel, B.BF16, c_high=2.0, state=state)
+    # gac_init zeroed the caller's state buffers: regenerate the reference in place
+    # (same per-tensor seeds, so the same bits as the host copies the oracle saw)
+    say("restoring the reference state")
+    for j, shp in enumerate(shapes):
+        gen_j = torch.Generator(device=DEV)
+        gen_j.manual_seed(W.tensor_seed(5, j))
+        state[j].copy_(torch.randn(shp, generator=gen_j, device=DEV, dtype=torch.float32).mul_(1e-3))
+    assert torch.equal(state[0][emb_rows], d0_emb)
+    ctx.gac_state_import(state, 0)  # same buffers: only resets the step counter
+    g_first = g[1].clone()
+    say("GPU step")
+    hyper = dict(lr=1e-6, beta1=0.9, beta2=0.999, eps_adam=1e-8, weight_decay=1e-2)
+    res = ctx.gac_step_adamw(g, p, m, v, None, t_adam=1, **hyper)
+    torch.cuda.synchronize()
+    check_result(res, s, dec)
+    assert res.regime == B.PROJECT
+    assert U.bits_equal(g[1], g_first), "the fused pass never writes g"
+    assert all(U.bits_equal(a, b) for a, b in zip(state, g)), "state must be the raw gradient"
+    say("oracle AdamW on sampled tensors")
+
+    def check(gj, dj, pj, mj, vj, p_new, m_new, v_new):
+        gp = O.project_rank_one(gj, dj, B.BF16, s, dec.alpha)
+        po, mo, vo = O.adamw(gp, pj, mj, vj, hyper["lr"], 0.9, 0.999, 1e-8, 1e-2, 1)
+        pg, mg, vg = (t.cpu().reshape(-1).double().numpy() for t in (p_new, m_new, v_new))
+        assert np.linalg.norm(mg - mo) <= 1e-6 * np.linalg.norm(mo)
+        assert np.linalg.norm(vg - vo) <= 1e-6 * np.linalg.norm(vo)
+        tol = U.adamw_param_tolerance(pj, mj, vo, gp, hyper["lr"], 0.9, 0.999, 1e-8, 1)
+        assert np.max(np.abs(pg - po) - tol) <= 0.0
+
+    for j in sample:
+        check(g_h[j], d_h[j], *keep[j], p[j], m[j], v[j])
+    n_emb = 4096 * shapes[0][1]
+    check(np.ascontiguousarray(g_h[0][:n_emb]), np.ascontiguousarray(d_h[0][:n_emb]), *keep_emb,
+          p[0][emb_rows], m[0][emb_rows], v[0][emb_rows])
+    say(f"  c={res.c:.6f} alpha={res.alpha:.6f}")
+    ctx.close()
