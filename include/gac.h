@@ -74,8 +74,9 @@ typedef struct gac_config {
   int32_t chunk_elems;     /* tuning: elements per work item of a block; 0 = default.
                               Must be a positive multiple of 2048. */
   int32_t grid_blocks;     /* tuning: workgroups of the reduction launch (= number of partial
-                              sums, so it is part of what fixes the result bits); 0 = default */
-  int32_t apply_blocks;    /* tuning: workgroups of the apply launch; 0 = default */
+                              sums, so it is part of what fixes the result bits); 0 = default
+                              (one per CU) */
+  int32_t apply_blocks;    /* tuning: workgroups of the apply launch; 0 = default (3/4 of the CUs) */
 } gac_config;
 
 typedef struct gac_result {

@@ -71,7 +71,8 @@ struct gac_ctx {
   int64_t n_chunks = 0;
   int64_t total = 0;
   int chunk_elems = 0;
-  int grid = 1;        // workgroups of the reduce, AdamW and state kernels (= number of partials)
+  int grid = 1;        // workgroups of the reduce kernel (= number of partials)
+  int grid_state = 1;  // workgroups of the state maintenance kernel
   int grid_apply = 1;  // workgroups of the apply kernel
   int grid_adamw = 1;  // workgroups of the fused AdamW apply kernel
   double c_low = 0, c_high = 0, eps = 0, beta = 1;
@@ -241,7 +242,7 @@ int state_op(gac_ctx* ctx, int op, const void* const* src, void* const* dst, hip
   int rc = upload_segs(ctx, src, dst, stream);
   if (rc != GAC_OK) return rc;
   GAC_HIP(ctx, gac::launch_state_op(ctx->dtype, op, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
-                                    ctx->grid, stream));
+                                    ctx->grid_state, stream));
   return GAC_OK;
 }
 
@@ -362,17 +363,21 @@ int gac_init(gac_ctx** out, const gac_config* cfg) {
   DeviceGuard guard(dev);
   hipDeviceProp_t prop;
   GAC_HIP(ctx, hipGetDeviceProperties(&prop, dev));
-  auto pick_grid = [&](int requested, int blocks_per_cu) {
-    int64_t g = requested > 0 ? requested
-                              : static_cast<int64_t>(prop.multiProcessorCount) * blocks_per_cu;
+  auto pick_grid = [&](int requested, int64_t by_default) {
+    int64_t g = requested > 0 ? requested : by_default;
     if (g > ctx->n_chunks) g = ctx->n_chunks;
     if (g < 1) g = 1;
     if (g > gac::kMaxGridBlocks) g = gac::kMaxGridBlocks;
     return static_cast<int>(g);
   };
-  ctx->grid = pick_grid(cfg->grid_blocks, gac::reduce_blocks_per_cu(ctx->dtype));
-  ctx->grid_apply = pick_grid(cfg->apply_blocks, gac::apply_blocks_per_cu(ctx->dtype));
-  ctx->grid_adamw = pick_grid(cfg->apply_blocks, gac::adamw_blocks_per_cu(ctx->dtype));
+  // Default grids (persistent kernels, static striding), from measurements on MI355X: the
+  // reduction does best with one workgroup per CU, the in-place pass with workgroups on
+  // three quarters of the CUs; more requesters lower the achieved HBM bandwidth.
+  const int64_t cus = prop.multiProcessorCount;
+  ctx->grid = pick_grid(cfg->grid_blocks, cus);
+  ctx->grid_state = pick_grid(0, cus * 4);
+  ctx->grid_apply = pick_grid(cfg->apply_blocks, cus * 3 / 4);
+  ctx->grid_adamw = pick_grid(cfg->apply_blocks, cus * gac::adamw_blocks_per_cu(ctx->dtype));
 
   ctx->state.assign(n, nullptr);
   if (cfg->state_ptrs != nullptr) {

@@ -50,10 +50,8 @@ constexpr int kMaxGridBlocks = 1 << 16;   // upper bound on workgroups per launc
 
 enum StateOp { kStateZero = 0, kStateCopy = 1 };
 
-// How many workgroups of the reduce / apply kernel are resident on one CU at a time; the
-// default grids are one resident wave of workgroups (persistent kernels, static striding).
-int reduce_blocks_per_cu(int dtype);
-int apply_blocks_per_cu(int dtype);
+// How many workgroups of the fused AdamW kernel are resident on one CU at a time (its
+// default grid is one resident wave of workgroups).
 int adamw_blocks_per_cu(int dtype);
 
 // Launchers (defined in gac_kernels.hip).  Each validates nothing: the host side has

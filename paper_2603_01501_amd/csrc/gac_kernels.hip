@@ -15,7 +15,7 @@
 // index order, so results are bit-reproducible.  No floating-point atomics anywhere.
 //
 // Accumulation: products are formed and summed in fp32 over one group of at most
-// kUnroll * 8 elements per lane (for bf16 inputs each product is exact in fp32), then the
+// GAC_REDUCE_UNROLL * 8 elements per lane (for bf16 inputs each product is exact in fp32), then the
 // group sum is widened and accumulated in fp64 per lane; wave, workgroup and grid combines
 // are fp64.
 
@@ -39,16 +39,19 @@ typedef GAC_GLOBAL uint16_t gu16;
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-// Tuning constants (chosen from measurements on MI355X; see the measurement notes of the
-// repository).  Pass 1 is a pure read stream: 256-thread workgroups, 4 x 16 B loads per
-// array in flight per lane, non-temporal loads.  Pass 2 reads and writes the same lines: it
-// does best with few, large workgroups that load a whole 64 KiB chunk of each array and
-// then store it (1024 threads x 4 vectors), non-temporal loads and stores.
+// Tuning constants, chosen from A/B measurements on MI355X with the tensors held fixed.
+// Both passes saturate HBM with FEW workgroups that each keep many 16-byte accesses in
+// flight; more resident waves only add contention at the memory controllers.
+// Pass 1 is a pure read stream: one 256-thread workgroup per CU, 8 x 16 B loads per array
+// in flight per lane, non-temporal loads (7.2 TB/s; 6.7 with six workgroups per CU).
+// Pass 2 reads and writes the same lines: 1024-thread workgroups that load a whole 64 KiB
+// chunk of each array and then store it (4 vectors per lane), on 3/4 of the CUs,
+// non-temporal loads and stores (5.4 TB/s; 5.3 on all CUs; 5.0 with 256-thread workgroups).
 #ifndef GAC_REDUCE_THREADS
 #define GAC_REDUCE_THREADS 256
 #endif
 #ifndef GAC_REDUCE_UNROLL
-#define GAC_REDUCE_UNROLL 4
+#define GAC_REDUCE_UNROLL 8
 #endif
 #ifndef GAC_REDUCE_NT_LOAD
 #define GAC_REDUCE_NT_LOAD 1
@@ -838,17 +841,7 @@ __global__ __launch_bounds__(kThreads) void state_kernel(const Seg* __restrict__
 
 }  // namespace
 
-// Workgroups of each kernel that fit on one CU at the same time (registers, LDS, threads).
-int reduce_blocks_per_cu(int dtype) {
-  int n = 0;
-  hipError_t e = dtype == GAC_F32
-      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(
-            &n, reduce_kernel<GAC_F32, GAC_REDUCE_THREADS, GAC_REDUCE_UNROLL>, GAC_REDUCE_THREADS, 0)
-      : hipOccupancyMaxActiveBlocksPerMultiprocessor(
-            &n, reduce_kernel<GAC_BF16, GAC_REDUCE_THREADS, GAC_REDUCE_UNROLL>, GAC_REDUCE_THREADS, 0);
-  return (e == hipSuccess && n > 0) ? n : 1;
-}
-
+// Workgroups of the fused AdamW kernel that fit on one CU at the same time.
 int adamw_blocks_per_cu(int dtype) {
   int n = 0;
   hipError_t e = dtype == GAC_F32
@@ -856,16 +849,6 @@ int adamw_blocks_per_cu(int dtype) {
             &n, apply_adamw_kernel<GAC_F32, GAC_ADAMW_THREADS>, GAC_ADAMW_THREADS, 0)
       : hipOccupancyMaxActiveBlocksPerMultiprocessor(
             &n, apply_adamw_kernel<GAC_BF16, GAC_ADAMW_THREADS>, GAC_ADAMW_THREADS, 0);
-  return (e == hipSuccess && n > 0) ? n : 1;
-}
-
-int apply_blocks_per_cu(int dtype) {
-  int n = 0;
-  hipError_t e = dtype == GAC_F32
-      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(
-            &n, apply_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL>, GAC_APPLY_THREADS, 0)
-      : hipOccupancyMaxActiveBlocksPerMultiprocessor(
-            &n, apply_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL>, GAC_APPLY_THREADS, 0);
   return (e == hipSuccess && n > 0) ? n : 1;
 }
 
