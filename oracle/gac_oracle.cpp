@@ -18,6 +18,12 @@
 //     initialised to zero ....................... Algorithm 1, Appendix A.2
 //   * AdamW hyper-parameters .................... Table 2 (the update rule
 //     itself is the textbook decoupled-weight-decay Adam)
+//   * gradient clipping ......................... Table 2 lists it as on, without
+//     order or threshold: read as global-norm clipping of the gradient GAC hands
+//     to the optimizer, scale = min(1, max_norm / (norm + 1e-6)) (the convention
+//     of the framework the paper builds on)
+//   * alignment statistics ...................... Table 3: q0.9(|c_t|), max |c_t|,
+//     Pr(|c_t| <= 0.05) over the updates after a burn-in
 //
 // Readings taken where the paper is silent are listed next to each function.
 // Parity status: every function here is pinned by tests that do not go through
@@ -26,9 +32,11 @@
 // except the non-finite convention of gac_oracle_decide, which the paper does
 // not define.
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <vector>
 
 namespace {
 
@@ -221,6 +229,47 @@ void gac_oracle_adamw(const double* g, const float* p, const float* m,
     v_out[i] = vi;
     p_out[i] = pi;
   }
+}
+
+// Global-norm clipping of the gradient list the optimizer is about to see (fp64, in place).
+// norm = sqrt(sum over all tensors and elements of g^2); scale = max_norm / (norm + 1e-6),
+// applied only when it is below 1.  Returns the scale that was applied (1 if none).
+double gac_oracle_clip(int32_t n_tensors, double* const* g, const int64_t* numel,
+                       double max_norm, double* norm_out) {
+  double sq = 0.0;
+  for (int32_t j = 0; j < n_tensors; ++j)
+    for (int64_t i = 0; i < numel[j]; ++i) sq += g[j][i] * g[j][i];
+  const double norm = std::sqrt(sq);
+  if (norm_out != nullptr) *norm_out = norm;
+  double scale = max_norm / (norm + 1e-6);
+  if (!(scale < 1.0)) return 1.0;
+  for (int32_t j = 0; j < n_tensors; ++j)
+    for (int64_t i = 0; i < numel[j]; ++i) g[j][i] *= scale;
+  return scale;
+}
+
+// Table 3 statistics of a run's cosines c_1 .. c_n: over the updates AFTER the first
+// `burn_in` ones, the q-quantile of |c_t| (linear interpolation between order statistics
+// at position (m-1) q, m = number of values), the maximum of |c_t| and the fraction with
+// |c_t| <= c_low.  NaN entries (non-finite steps) are left out.  out = {quantile, max,
+// fraction, m}; with m = 0 the first three are 0.
+void gac_oracle_alignment_stats(const double* c, int64_t n, int64_t burn_in, double c_low,
+                                double q, double out[4]) {
+  std::vector<double> a;
+  for (int64_t t = burn_in; t < n; ++t)
+    if (!std::isnan(c[t])) a.push_back(std::fabs(c[t]));
+  out[0] = out[1] = out[2] = 0.0;
+  out[3] = static_cast<double>(a.size());
+  if (a.empty()) return;
+  std::sort(a.begin(), a.end());
+  const double pos = (static_cast<double>(a.size()) - 1.0) * q;
+  const size_t lo = static_cast<size_t>(std::floor(pos));
+  const size_t hi = std::min(lo + 1, a.size() - 1);
+  out[0] = a[lo] + (a[hi] - a[lo]) * (pos - static_cast<double>(lo));
+  out[1] = a.back();
+  int64_t inside = 0;
+  for (double x : a) inside += (x <= c_low) ? 1 : 0;
+  out[2] = static_cast<double>(inside) / static_cast<double>(a.size());
 }
 
 }  // extern "C"

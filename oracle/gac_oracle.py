@@ -81,6 +81,11 @@ def lib() -> ctypes.CDLL:
         L.gac_oracle_adamw.argtypes = [dp, fp, fp, fp, ctypes.c_int64] + [ctypes.c_double] * 5 + \
                                       [ctypes.c_int64, dp, dp, dp]
         L.gac_oracle_adamw.restype = None
+        L.gac_oracle_clip.argtypes = [ctypes.c_int32, ctypes.POINTER(dp), i64p, ctypes.c_double, dp]
+        L.gac_oracle_clip.restype = ctypes.c_double
+        L.gac_oracle_alignment_stats.argtypes = [dp, ctypes.c_int64, ctypes.c_int64, ctypes.c_double,
+                                                 ctypes.c_double, dp]
+        L.gac_oracle_alignment_stats.restype = None
         _lib = L
     return _lib
 
@@ -187,3 +192,23 @@ def adamw(g: np.ndarray, p: np.ndarray, m: np.ndarray, v: np.ndarray, lr: float,
                            v.ctypes.data_as(fp), n, lr, beta1, beta2, eps_adam, weight_decay,
                            int(t), _dp(po), _dp(mo), _dp(vo))
     return po, mo, vo
+
+
+def clip(g: Sequence[np.ndarray], max_norm: float):
+    """Global-norm clipping of a list of fp64 arrays in place; returns (scale applied, norm)."""
+    for a in g:
+        if a.dtype != np.float64 or not a.flags["C_CONTIGUOUS"]:
+            raise TypeError("clip works on contiguous float64 arrays")
+    n = len(g)
+    ptrs = (ctypes.POINTER(ctypes.c_double) * n)(*[_dp(a) for a in g])
+    norm = ctypes.c_double(0.0)
+    scale = lib().gac_oracle_clip(n, ptrs, _numel(g), max_norm, ctypes.byref(norm))
+    return scale, norm.value
+
+
+def alignment_stats(c: np.ndarray, burn_in: int, c_low: float, q: float = 0.9):
+    """(q-quantile of |c|, max |c|, fraction with |c| <= c_low, count) after the burn-in."""
+    c = np.ascontiguousarray(c, dtype=np.float64)
+    out = np.zeros(4, dtype=np.float64)
+    lib().gac_oracle_alignment_stats(_dp(c), c.size, burn_in, c_low, q, _dp(out))
+    return float(out[0]), float(out[1]), float(out[2]), int(out[3])

@@ -25,6 +25,11 @@ MUTATIONS = [
     ("state_not_updated_on_skip", "if (!dec.nonfinite) {", "if (!dec.nonfinite && dec.regime != ORACLE_SKIP) {"),
     ("bf16_low_half", "static_cast<uint32_t>(h) << 16;", "static_cast<uint32_t>(h) << 15;"),
     ("adam_no_bias_correction2", "std::sqrt(vi / bc2)", "std::sqrt(vi)"),
+    ("clip_eps_dropped", "double scale = max_norm / (norm + 1e-6);", "double scale = max_norm / norm;"),
+    ("clip_always_scales", "if (!(scale < 1.0)) return 1.0;", "if (false) return 1.0;"),
+    ("quantile_nearest_rank", "out[0] = a[lo] + (a[hi] - a[lo]) * (pos - static_cast<double>(lo));", "out[0] = a[hi];"),
+    ("stats_ignore_burn_in", "for (int64_t t = burn_in; t < n; ++t)", "for (int64_t t = 0; t < n; ++t)"),
+    ("stats_strict_threshold", "inside += (x <= c_low) ? 1 : 0;", "inside += (x < c_low) ? 1 : 0;"),
     ("adam_coupled_decay", "pi = pi - lr * weight_decay * pi;", "pi = pi - weight_decay * pi;"),
 ]
 

@@ -350,3 +350,55 @@ def test_adamw_table2_hyperparameters_first_step_closed_form():
     np.testing.assert_allclose(po, want, rtol=1e-15)
     np.testing.assert_allclose(mo, 0.1 * g, rtol=1e-15)
     np.testing.assert_allclose(vo, 0.001 * g * g, rtol=1e-12)
+
+
+# ---------------------------------------------------------------- clipping, alignment statistics
+
+def test_clip_against_torch_clip_grad_norm():
+    rng = np.random.default_rng(21)
+    arrs = [rng.standard_normal(n) for n in (100, 1, 777)]
+    for max_norm in (0.5, 5.0, 1e6):
+        mine = [a.copy() for a in arrs]
+        scale, norm = O.clip(mine, max_norm)
+        params = [torch.nn.Parameter(torch.zeros(a.size, dtype=torch.float64)) for a in arrs]
+        for q, a in zip(params, arrs):
+            q.grad = torch.tensor(a)
+        total = torch.nn.utils.clip_grad_norm_(params, max_norm)
+        assert norm == pytest.approx(float(total), rel=1e-14)
+        for a, q in zip(mine, params):
+            np.testing.assert_allclose(a, q.grad.numpy(), rtol=1e-14, atol=0)
+        assert (scale < 1.0) == (max_norm < norm)
+
+
+def test_clip_closed_form():
+    g = [np.array([3.0, 0.0]), np.array([4.0])]          # norm 5
+    scale, norm = O.clip(g, 1.0)
+    assert norm == 5.0 and scale == pytest.approx(1.0 / (5.0 + 1e-6), rel=1e-15)
+    assert math.sqrt(sum(float(np.dot(a, a)) for a in g)) == pytest.approx(5.0 / (5.0 + 1e-6), rel=1e-15)
+    g = [np.array([3.0, 0.0]), np.array([4.0])]
+    assert O.clip(g, 7.0)[0] == 1.0 and g[0].tolist() == [3.0, 0.0]   # below the threshold: untouched
+    # exactly at the threshold the 1e-6 in the denominator still scales, by 5/(5+1e-6)
+    assert O.clip(g, 5.0)[0] == pytest.approx(5.0 / (5.0 + 1e-6), rel=1e-15)
+
+
+def test_alignment_stats_against_numpy():
+    rng = np.random.default_rng(22)
+    c = rng.standard_normal(500) * 0.04
+    c[7] = float("nan")
+    c[300] = float("nan")
+    for burn in (0, 50, 499):
+        q, mx, frac, m = O.alignment_stats(c, burn, 0.05)
+        a = np.abs(c[burn:])
+        a = a[~np.isnan(a)]
+        assert m == a.size
+        assert q == pytest.approx(float(np.quantile(a, 0.9)), rel=1e-14)
+        assert mx == float(a.max()) and frac == pytest.approx(float(np.mean(a <= 0.05)), rel=1e-15)
+    assert O.alignment_stats(c, 500, 0.05) == (0.0, 0.0, 0.0, 0)
+
+
+def test_alignment_stats_hand_example():
+    # |c| sorted: 0.01 0.02 0.03 0.04 0.10 ; position (5-1)*0.9 = 3.6 -> 0.04 + 0.6*(0.10-0.04)
+    c = np.array([0.5, -0.04, 0.01, -0.10, 0.03, 0.02])      # the first one is burned in
+    q, mx, frac, m = O.alignment_stats(c, 1, 0.03)
+    assert (m, mx) == (5, 0.10)
+    assert q == pytest.approx(0.076, rel=1e-14) and frac == pytest.approx(3 / 5)
