@@ -14,6 +14,9 @@
  *      alpha = c_low/|c|, beta = 1                   (Eq. 2-4, Appendix A.2),
  *   5. d <- raw g of this step: the reference of the next step
  *      (Algorithm 1 initialises it to zero; Appendix A.2 "gradient snapshot").
+ * Optional, both off by default: global-norm clipping of the gradient handed to the optimizer
+ * folded into step 4 without another pass (Table 2 lists gradient clipping as on), and a
+ * per-step record of c_t with the statistics of Table 3 (gac_diag_summary).
  *
  * General rules
  *   - Every pointer named "device" is GPU memory owned by the caller (for
@@ -77,6 +80,13 @@ typedef struct gac_config {
                               sums, so it is part of what fixes the result bits); 0 = default
                               (one per CU) */
   int32_t apply_blocks;    /* tuning: workgroups of the apply launch; 0 = default (3/4 of the CUs) */
+  double max_grad_norm;    /* > 0: the gradient handed to the optimizer (g' when projected, g when
+                              safe) is scaled by min(1, max_grad_norm / (its 2-norm + 1e-6)); the
+                              norm comes from the three sums, so no extra pass.  0 = no clipping.
+                              The reference state always keeps the raw, unclipped gradient. */
+  int32_t history_capacity;/* steps of (c_t, regime) kept on the device for gac_history_read /
+                              gac_diag_summary; 0 = default 1024; at most 4096 */
+  int32_t reserved;        /* must be 0 */
 } gac_config;
 
 typedef struct gac_result {
@@ -86,10 +96,30 @@ typedef struct gac_result {
   double c;    /* cosine with eps; NaN if nonfinite */
   double alpha;/* c_low/|c| in the projection regime, else 1 */
   double coef; /* k in g' = beta g + k d;  (alpha-beta) <g,d>/<d,d> in the projection regime, else 0 */
+  double grad_norm; /* 2-norm of the gradient GAC hands over, before clipping: |g'| when
+                       projected (from the sums: beta^2<g,g> + 2 beta k <g,d> + k^2 <d,d>), else |g| */
+  double clip_coef; /* factor applied by clipping, 1 if none (or clipping off, or GAC_SKIP) */
+  double scale_g;   /* what pass 2 actually computes is  scale_g * g + coef_d * d : */
+  double coef_d;    /*   scale_g = clip_coef * (beta if projected else 1), coef_d = clip_coef * coef */
   int32_t regime;    /* GAC_SAFE / GAC_PROJECT / GAC_SKIP */
   int32_t nonfinite; /* 1 if any sum was not finite */
+  int32_t modified;  /* 1 if the gradient for the optimizer differs from the raw g (projected
+                        and/or clipped): gac_step has overwritten g; gac_step_exchange has put it
+                        into the returned buffers */
+  int32_t reserved;
   int64_t step;      /* 1 for the first update after init/reset */
 } gac_result;
+
+/* Statistics of the recorded cosines, as in Table 3 of the paper (computed on the GPU). */
+typedef struct gac_diag {
+  int64_t first_step, last_step; /* range of recorded steps that was looked at (after burn-in) */
+  int64_t n_values;              /* steps in that range with a finite c_t */
+  int64_t n_nonfinite;           /* steps in that range whose sums were not finite */
+  int64_t regime_count[3];       /* safe / projected / skipped steps in that range */
+  double q90_abs_c;              /* 0.9-quantile of |c_t| (linear interpolation between order statistics) */
+  double max_abs_c;
+  double frac_le_c_low;          /* fraction of steps with |c_t| <= c_low (the current c_low) */
+} gac_diag;
 
 /* AdamW hyper-parameters; the paper's values are lr 1e-6, betas (0.9, 0.999),
  * eps 1e-8, weight decay 1e-2 (Table 2).  t_adam is the 1-based count of optimizer
@@ -128,10 +158,11 @@ int gac_step(gac_ctx* ctx, void* const* grad_ptrs, void* hip_stream, gac_result*
  * host_out != NULL.  The g buffers passed in BECOME the reference state (the raw gradient is
  * the next reference: Algorithm 1, Appendix A.2) and the buffers that held the previous
  * reference state are returned in grad_ptrs:
- *   GAC_PROJECT  the returned buffers hold the projected gradient g' (Eq. 4): give those to
- *                the optimizer.  Traffic: 2 N s (statistics) + 3 N s instead of 6 N s.
- *   GAC_SAFE     the gradient to use is still in the buffers that were passed in; they now
- *                belong to the library and must only be read.  GAC_SKIP: no update.
+ *   modified = 1 (projected, or clipped): the returned buffers hold the gradient for the
+ *                optimizer (g' of Eq. 4, times the clip factor).  Traffic: 2 N s (statistics)
+ *                + 3 N s instead of 6 N s.
+ *   modified = 0 GAC_SAFE: the gradient to use is still in the buffers that were passed in;
+ *                they now belong to the library and must only be read.  GAC_SKIP: no update.
  *                Nothing is moved at all (2 N s for the statistics only); the content of the
  *                returned buffers is unspecified.
  * In every regime the returned buffers are free for the caller's next gradient once the
@@ -178,6 +209,18 @@ int gac_reset(gac_ctx* ctx, void* hip_stream);
 
 /* Replaces the thresholds (validated as in gac_init) for the following steps. */
 int gac_set_thresholds(gac_ctx* ctx, double c_low, double c_high);
+
+/* Copies the most recent recorded steps (oldest first, at most max_n) to host arrays: c_out
+ * gets c_t (NaN for a non-finite step), regime_out the regime; either may be NULL.  n_out
+ * receives the count and first_step_out the step number of the first entry.  Waits for the
+ * stream.  Records start again after gac_reset / gac_state_import. */
+int gac_history_read(gac_ctx* ctx, int64_t max_n, double* c_out, int32_t* regime_out,
+                     int64_t* n_out, int64_t* first_step_out, void* hip_stream);
+
+/* The statistics the paper uses to place its thresholds (Table 3: q0.9(|c_t|), max |c_t| and
+ * Pr(|c_t| <= c_low) "over updates after step 50"), over the recorded steps with step number
+ * > burn_in.  One small kernel on the stream; waits for it. */
+int gac_diag_summary(gac_ctx* ctx, int64_t burn_in, gac_diag* out, void* hip_stream);
 
 /* Host-only planning query (no GPU call): the number of work items the tensor list is cut
  * into (no item straddles two tensors) and the total element count.  chunk_elems = 0 uses

@@ -32,16 +32,27 @@ class GacConfig(ctypes.Structure):
                 ("numel", ctypes.POINTER(ctypes.c_int64)), ("state_ptrs", ctypes.POINTER(ctypes.c_void_p)),
                 ("device", ctypes.c_int32), ("flags", ctypes.c_uint32),
                 ("chunk_elems", ctypes.c_int32), ("grid_blocks", ctypes.c_int32),
-                ("apply_blocks", ctypes.c_int32)]
+                ("apply_blocks", ctypes.c_int32), ("max_grad_norm", ctypes.c_double),
+                ("history_capacity", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class GacResult(ctypes.Structure):
     _fields_ = [("dot", ctypes.c_double), ("gg", ctypes.c_double), ("dd", ctypes.c_double),
                 ("c", ctypes.c_double), ("alpha", ctypes.c_double), ("coef", ctypes.c_double),
-                ("regime", ctypes.c_int32), ("nonfinite", ctypes.c_int32), ("step", ctypes.c_int64)]
+                ("grad_norm", ctypes.c_double), ("clip_coef", ctypes.c_double),
+                ("scale_g", ctypes.c_double), ("coef_d", ctypes.c_double),
+                ("regime", ctypes.c_int32), ("nonfinite", ctypes.c_int32),
+                ("modified", ctypes.c_int32), ("reserved", ctypes.c_int32), ("step", ctypes.c_int64)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+class GacDiag(ctypes.Structure):
+    _fields_ = [("first_step", ctypes.c_int64), ("last_step", ctypes.c_int64),
+                ("n_values", ctypes.c_int64), ("n_nonfinite", ctypes.c_int64),
+                ("regime_count", ctypes.c_int64 * 3), ("q90_abs_c", ctypes.c_double),
+                ("max_abs_c", ctypes.c_double), ("frac_le_c_low", ctypes.c_double)]
 
 
 class GacAdamWHyper(ctypes.Structure):
@@ -91,6 +102,8 @@ def lib() -> ctypes.CDLL:
         "gac_state_import": (ctypes.c_int, [vp, vpp, ctypes.c_int64, vp]),
         "gac_reset": (ctypes.c_int, [vp, vp]),
         "gac_set_thresholds": (ctypes.c_int, [vp, ctypes.c_double, ctypes.c_double]),
+        "gac_history_read": (ctypes.c_int, [vp, ctypes.c_int64, dp, ctypes.POINTER(ctypes.c_int32), i64p, i64p, vp]),
+        "gac_diag_summary": (ctypes.c_int, [vp, ctypes.c_int64, ctypes.POINTER(GacDiag), vp]),
         "gac_plan_query": (ctypes.c_int, [i64p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, i64p, i64p]),
         "gac_profile_enable": (ctypes.c_int, [vp, ctypes.c_int32]),
         "gac_profile_read": (ctypes.c_int, [vp, dp, dp, dp, ctypes.POINTER(ctypes.c_int32)]),
@@ -146,7 +159,8 @@ class Gac:
 
     def __init__(self, numel: Sequence[int], dtype: int, c_low: float = 0.05, c_high: float = 0.3,
                  eps: float = 1e-8, beta: float = 1.0, state: Optional[Sequence] = None,
-                 device: int = -1, chunk_elems: int = 0, grid_blocks: int = 0, apply_blocks: int = 0):
+                 device: int = -1, chunk_elems: int = 0, grid_blocks: int = 0, apply_blocks: int = 0,
+                 max_grad_norm: float = 0.0, history_capacity: int = 0):
         L = lib()
         cfg = GacConfig()
         L.gac_default_config(ctypes.byref(cfg))
@@ -160,6 +174,7 @@ class Gac:
             cfg.state_ptrs = ctypes.cast(self._state_ptrs, ctypes.POINTER(ctypes.c_void_p))
         cfg.device, cfg.chunk_elems, cfg.grid_blocks = device, chunk_elems, grid_blocks
         cfg.apply_blocks = apply_blocks
+        cfg.max_grad_norm, cfg.history_capacity = max_grad_norm, history_capacity
         self._ctx = ctypes.c_void_p()
         rc = L.gac_init(ctypes.byref(self._ctx), ctypes.byref(cfg))
         if rc != OK:
@@ -251,6 +266,20 @@ class Gac:
 
     def gac_set_thresholds(self, c_low: float, c_high: float) -> None:
         self._check(lib().gac_set_thresholds(self._ctx, c_low, c_high))
+
+    def gac_history_read(self, max_n: int = 4096, stream=None):
+        """(list of c_t, list of regimes, step number of the first entry), oldest first."""
+        c = (ctypes.c_double * max_n)()
+        r = (ctypes.c_int32 * max_n)()
+        n, first = ctypes.c_int64(0), ctypes.c_int64(0)
+        self._check(lib().gac_history_read(self._ctx, max_n, c, r, ctypes.byref(n), ctypes.byref(first),
+                                           _stream_handle(stream)))
+        return list(c[:n.value]), list(r[:n.value]), first.value
+
+    def gac_diag_summary(self, burn_in: int = 0, stream=None) -> GacDiag:
+        d = GacDiag()
+        self._check(lib().gac_diag_summary(self._ctx, burn_in, ctypes.byref(d), _stream_handle(stream)))
+        return d
 
     def gac_profile_enable(self, on: bool) -> None:
         self._check(lib().gac_profile_enable(self._ctx, 1 if on else 0))

@@ -76,7 +76,17 @@ struct gac_ctx {
   int grid_apply = 1;  // workgroups of the apply kernel
   int grid_adamw = 1;  // workgroups of the fused AdamW apply kernel
   double c_low = 0, c_high = 0, eps = 0, beta = 1;
+  double max_grad_norm = 0;
   int64_t step = 0;
+
+  // record of (c_t, regime) per step: a ring on the device, written by the finalize kernel
+  double* hist_c = nullptr;
+  int32_t* hist_regime = nullptr;
+  int hist_cap = 0;
+  int64_t hist_first = 1;  // earliest step number whose record is valid (moves on reset / import)
+  gac_diag* dev_diag = nullptr;
+  gac_diag* pinned_diag = nullptr;
+  gac_diag* pinned_diag_dev = nullptr;
 
   std::vector<void*> state;    // device pointers of d, one per tensor
   void* state_alloc = nullptr; // owned allocation backing `state`, or null
@@ -234,7 +244,11 @@ DecideParams decide_params(const gac_ctx* ctx) {
   p.c_high = ctx->c_high;
   p.eps = ctx->eps;
   p.beta = ctx->beta;
+  p.max_grad_norm = ctx->max_grad_norm;
   p.step = ctx->step;
+  p.hist_c = ctx->hist_c;
+  p.hist_regime = ctx->hist_regime;
+  p.hist_cap = ctx->hist_cap;
   return p;
 }
 
@@ -271,17 +285,16 @@ int run_step(gac_ctx* ctx, void* const* grad_ptrs, bool do_reduce, const double*
     if (rc != GAC_OK) return rc;
   }
   if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[2], stream));
-  const float beta = static_cast<float>(ctx->beta);
   if (kind == ApplyKind::kExchange) {
     GAC_HIP(ctx, gac::launch_exchange(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
-                                      ctx->chunk_elems, ctx->dev_result, beta, ctx->grid_apply, stream));
+                                      ctx->chunk_elems, ctx->dev_result, ctx->grid_apply, stream));
   } else if (kind == ApplyKind::kPlain) {
     GAC_HIP(ctx, gac::launch_apply(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
-                                   ctx->chunk_elems, ctx->dev_result, beta, ctx->grid_apply, stream));
+                                   ctx->chunk_elems, ctx->dev_result, ctx->grid_apply, stream));
   } else {
     GAC_HIP(ctx, gac::launch_apply_adamw(ctx->dtype, ctx->dev_segs, ctx->dev_adam, ctx->n_tensors,
-                                         ctx->n_chunks, ctx->chunk_elems, ctx->dev_result, beta,
-                                         *adam, ctx->grid_adamw, stream));
+                                         ctx->n_chunks, ctx->chunk_elems, ctx->dev_result, *adam,
+                                         ctx->grid_adamw, stream));
   }
   if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[3], stream));
   if (host_out != nullptr) return wait_result(ctx, host_out);
@@ -323,10 +336,11 @@ int gac_init(gac_ctx** out, const gac_config* cfg) {
   *out = nullptr;
   if (cfg == nullptr || cfg->n_tensors < 0 || (cfg->n_tensors > 0 && cfg->numel == nullptr) ||
       cfg->flags != 0 || cfg->grid_blocks < 0 || cfg->grid_blocks > gac::kMaxGridBlocks ||
-      cfg->apply_blocks < 0 || cfg->apply_blocks > gac::kMaxGridBlocks)
+      cfg->apply_blocks < 0 || cfg->apply_blocks > gac::kMaxGridBlocks || cfg->reserved != 0 ||
+      cfg->history_capacity < 0 || cfg->history_capacity > gac::kMaxHistory)
     return GAC_ERR_INVALID_ARG;
   if (!thresholds_ok(cfg->c_low, cfg->c_high) || !(cfg->eps >= 0.0) || !(cfg->beta >= 0.0) ||
-      !std::isfinite(cfg->eps) || !std::isfinite(cfg->beta))
+      !std::isfinite(cfg->eps) || !std::isfinite(cfg->beta) || !(cfg->max_grad_norm >= 0.0))
     return GAC_ERR_BAD_THRESHOLDS;
   int chunk_elems = 0;
   int rc = resolve_chunk_elems(cfg->dtype, cfg->chunk_elems, &chunk_elems);
@@ -346,6 +360,8 @@ int gac_init(gac_ctx** out, const gac_config* cfg) {
   ctx->c_high = cfg->c_high;
   ctx->eps = cfg->eps;
   ctx->beta = cfg->beta;
+  ctx->max_grad_norm = cfg->max_grad_norm;
+  ctx->hist_cap = cfg->history_capacity > 0 ? cfg->history_capacity : 1024;
   const int n = cfg->n_tensors;
   ctx->numel.assign(cfg->numel, cfg->numel + n);
   rc = plan(ctx->numel.data(), n, chunk_elems, &ctx->first_chunk, &ctx->total);
@@ -422,6 +438,11 @@ int gac_init(gac_ctx** out, const gac_config* cfg) {
                                        ctx->pinned_result, 0));
   GAC_HIP(ctx, hipEventCreateWithFlags(&ctx->result_event, hipEventDisableTiming));
   std::memset(ctx->pinned_result, 0, sizeof(gac_result));
+  GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->hist_c), sizeof(double) * ctx->hist_cap));
+  GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->hist_regime), sizeof(int32_t) * ctx->hist_cap));
+  GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_diag), sizeof(gac_diag)));
+  GAC_HIP(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned_diag), sizeof(gac_diag), hipHostMallocMapped));
+  GAC_HIP(ctx, hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->pinned_diag_dev), ctx->pinned_diag, 0));
 
   // Algorithm 1: the reference state starts at zero.
   rc = state_op(ctx, gac::kStateZero, nullptr, ctx->state.data(), nullptr);
@@ -445,6 +466,10 @@ void gac_destroy(gac_ctx* ctx) {
     if (ctx->dev_sums) (void)hipFree(ctx->dev_sums);
     if (ctx->dev_result) (void)hipFree(ctx->dev_result);
     if (ctx->pinned_result) (void)hipHostFree(ctx->pinned_result);
+    if (ctx->hist_c) (void)hipFree(ctx->hist_c);
+    if (ctx->hist_regime) (void)hipFree(ctx->hist_regime);
+    if (ctx->dev_diag) (void)hipFree(ctx->dev_diag);
+    if (ctx->pinned_diag) (void)hipHostFree(ctx->pinned_diag);
     if (ctx->result_event) (void)hipEventDestroy(ctx->result_event);
     for (int s = 0; s < kPinnedSlots; ++s) {
       if (ctx->pinned_segs[s]) (void)hipHostFree(ctx->pinned_segs[s]);
@@ -495,7 +520,7 @@ int gac_reduce_local(gac_ctx* ctx, void* const* grad_ptrs, void* hip_stream, dou
   GAC_HIP(ctx, gac::launch_reduce(ctx->dtype, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
                                   ctx->dev_partials, ctx->grid, stream));
   GAC_HIP(ctx, gac::launch_finalize(ctx->dev_partials, ctx->grid, nullptr, dev_sums3, ctx->dev_result,
-                                    nullptr, decide_params(ctx), /*mode=*/1, stream));
+                                    nullptr, decide_params(ctx), /*mode=*/1, stream));  // sums only
   return GAC_OK;
 }
 
@@ -571,7 +596,10 @@ int gac_state_import(gac_ctx* ctx, void* const* src_ptrs, int64_t step, void* hi
   DeviceGuard guard(ctx->device);
   rc = state_op(ctx, gac::kStateCopy, const_cast<const void* const*>(src_ptrs), ctx->state.data(),
                 static_cast<hipStream_t>(hip_stream));
-  if (rc == GAC_OK) ctx->step = step;
+  if (rc == GAC_OK) {
+    ctx->step = step;
+    ctx->hist_first = step + 1;
+  }
   return rc;
 }
 
@@ -579,7 +607,10 @@ int gac_reset(gac_ctx* ctx, void* hip_stream) {
   if (ctx == nullptr) return GAC_ERR_INVALID_ARG;
   DeviceGuard guard(ctx->device);
   int rc = state_op(ctx, gac::kStateZero, nullptr, ctx->state.data(), static_cast<hipStream_t>(hip_stream));
-  if (rc == GAC_OK) ctx->step = 0;
+  if (rc == GAC_OK) {
+    ctx->step = 0;
+    ctx->hist_first = 1;
+  }
   return rc;
 }
 
@@ -588,6 +619,58 @@ int gac_set_thresholds(gac_ctx* ctx, double c_low, double c_high) {
   if (!thresholds_ok(c_low, c_high)) return GAC_ERR_BAD_THRESHOLDS;
   ctx->c_low = c_low;
   ctx->c_high = c_high;
+  return GAC_OK;
+}
+
+namespace {
+// Range of step numbers whose record is still in the ring.
+void recorded_range(const gac_ctx* ctx, int64_t* first, int64_t* last) {
+  *last = ctx->step;
+  int64_t f = ctx->step - ctx->hist_cap + 1;
+  if (f < ctx->hist_first) f = ctx->hist_first;
+  *first = f;
+}
+}  // namespace
+
+int gac_history_read(gac_ctx* ctx, int64_t max_n, double* c_out, int32_t* regime_out,
+                     int64_t* n_out, int64_t* first_step_out, void* hip_stream) {
+  if (ctx == nullptr || max_n < 0 || n_out == nullptr) return GAC_ERR_INVALID_ARG;
+  DeviceGuard guard(ctx->device);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  int64_t first, last;
+  recorded_range(ctx, &first, &last);
+  int64_t n = last >= first ? last - first + 1 : 0;
+  if (n > max_n) {
+    first += n - max_n;
+    n = max_n;
+  }
+  *n_out = n;
+  if (first_step_out) *first_step_out = first;
+  if (n == 0) return GAC_OK;
+  GAC_HIP(ctx, hipStreamSynchronize(stream));
+  std::vector<double> c(ctx->hist_cap);
+  std::vector<int32_t> r(ctx->hist_cap);
+  GAC_HIP(ctx, hipMemcpy(c.data(), ctx->hist_c, sizeof(double) * ctx->hist_cap, hipMemcpyDeviceToHost));
+  GAC_HIP(ctx, hipMemcpy(r.data(), ctx->hist_regime, sizeof(int32_t) * ctx->hist_cap, hipMemcpyDeviceToHost));
+  for (int64_t i = 0; i < n; ++i) {
+    const int slot = static_cast<int>((first + i - 1) % ctx->hist_cap);
+    if (c_out) c_out[i] = c[slot];
+    if (regime_out) regime_out[i] = r[slot] < 0 ? GAC_SKIP : r[slot];
+  }
+  return GAC_OK;
+}
+
+int gac_diag_summary(gac_ctx* ctx, int64_t burn_in, gac_diag* out, void* hip_stream) {
+  if (ctx == nullptr || out == nullptr || burn_in < 0) return GAC_ERR_INVALID_ARG;
+  DeviceGuard guard(ctx->device);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  int64_t first, last;
+  recorded_range(ctx, &first, &last);
+  if (first < burn_in + 1) first = burn_in + 1;
+  GAC_HIP(ctx, gac::launch_diag(ctx->hist_c, ctx->hist_regime, ctx->hist_cap, first, last, ctx->c_low,
+                                ctx->dev_diag, ctx->pinned_diag_dev, stream));
+  GAC_HIP(ctx, hipStreamSynchronize(stream));
+  *out = *ctx->pinned_diag;
   return GAC_OK;
 }
 

@@ -32,8 +32,14 @@ static_assert(sizeof(AdamSeg) == 32, "AdamSeg layout is shared with device code"
 // What the finalize kernel needs besides the partial sums.
 struct DecideParams {
   double c_low, c_high, eps, beta;
+  double max_grad_norm;  // 0 = no clipping
   int64_t step;
+  double* hist_c;        // ring of recorded cosines, hist_cap entries (or null)
+  int32_t* hist_regime;  // ring of recorded regimes
+  int32_t hist_cap;
 };
+
+constexpr int kMaxHistory = 4096;  // the statistics kernel sorts the ring in LDS
 
 // AdamW scalars, prepared on the host in fp64 and rounded once to fp32.
 struct AdamScalars {
@@ -66,17 +72,22 @@ hipError_t launch_finalize(const double* dev_partials, int n_partials, const dou
                            DecideParams p, int mode, hipStream_t stream);
 
 hipError_t launch_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
-                        int chunk_elems, const gac_result* dev_result, float beta, int grid,
-                        hipStream_t stream);
+                        int chunk_elems, const gac_result* dev_result, int grid, hipStream_t stream);
+
+// Table 3 statistics over ring entries of steps first_step .. last_step (1-based, at most
+// hist_cap of them); writes *dev_out and, if not null, *host_out (host-mapped).
+hipError_t launch_diag(const double* hist_c, const int32_t* hist_regime, int hist_cap,
+                       int64_t first_step, int64_t last_step, double c_low, gac_diag* dev_out,
+                       gac_diag* host_out, hipStream_t stream);
 
 // Buffer-exchange pass 2: writes g' over the old state (Seg::b) in the projection regime only.
 hipError_t launch_exchange(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
-                           int chunk_elems, const gac_result* dev_result, float beta, int grid,
+                           int chunk_elems, const gac_result* dev_result, int grid,
                            hipStream_t stream);
 
 hipError_t launch_apply_adamw(int dtype, const Seg* dev_segs, const AdamSeg* dev_adam,
                               int n_tensors, int64_t n_chunks, int chunk_elems,
-                              const gac_result* dev_result, float beta, AdamScalars h, int grid,
+                              const gac_result* dev_result, AdamScalars h, int grid,
                               hipStream_t stream);
 
 hipError_t launch_state_op(int dtype, int op, const Seg* dev_segs, int64_t n_chunks,

@@ -378,7 +378,13 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const double* __rest
   r.dd = s_dd;
   r.alpha = 1.0;
   r.coef = 0.0;
+  r.grad_norm = 0.0;
+  r.clip_coef = 1.0;
+  r.scale_g = 1.0;
+  r.coef_d = 0.0;
   r.nonfinite = 0;
+  r.modified = 0;
+  r.reserved = 0;
   r.step = p.step;
   if (!(isfinite(s_gd) && isfinite(s_gg) && isfinite(s_dd))) {
     r.c = __longlong_as_double(0x7ff8000000000000LL);
@@ -389,7 +395,8 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const double* __rest
     const double c = s_gd / (sqrt(s_gg * s_dd) + p.eps);
     const double mag = fabs(c);
     r.c = c;
-    if (mag <= p.c_low) {  // Algorithm 1 tests the safe branch first
+    double norm_sq = s_gg;  // squared norm of the gradient handed to the optimizer
+    if (mag <= p.c_low) {   // Algorithm 1 tests the safe branch first
       r.regime = GAC_SAFE;
     } else if (mag >= p.c_high) {
       r.regime = GAC_SKIP;
@@ -399,7 +406,27 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const double* __rest
       // <g,u> u = (<g,d>/<d,d>) d, so g' = beta g + (alpha - beta)(<g,d>/<d,d>) d.
       // |c| > c_low > 0 implies <d,d> > 0.
       r.coef = (r.alpha - p.beta) * (s_gd / s_dd);
+      r.scale_g = p.beta;
+      r.coef_d = r.coef;
+      r.modified = 1;
+      // |beta g + k d|^2 from the three sums: no further pass over the data
+      norm_sq = p.beta * p.beta * s_gg + 2.0 * p.beta * r.coef * s_gd + r.coef * r.coef * s_dd;
     }
+    r.grad_norm = sqrt(norm_sq > 0.0 ? norm_sq : 0.0);
+    if (p.max_grad_norm > 0.0 && r.regime != GAC_SKIP) {
+      const double clip = p.max_grad_norm / (r.grad_norm + 1e-6);
+      if (clip < 1.0) {
+        r.clip_coef = clip;
+        r.scale_g *= clip;
+        r.coef_d *= clip;
+        r.modified = 1;
+      }
+    }
+  }
+  if (p.hist_c != nullptr) {
+    const int slot = static_cast<int>((p.step - 1) % p.hist_cap);
+    p.hist_c[slot] = r.c;
+    p.hist_regime[slot] = r.nonfinite ? -1 : r.regime;
   }
   *res = r;
   // Optional second copy straight into host-mapped pinned memory: the host then learns the
@@ -477,12 +504,13 @@ template <int DT, int T, int U>
 __global__ __launch_bounds__(T) void apply_kernel(const Seg* __restrict__ segs,
                                                          int n_tensors, int64_t n_chunks,
                                                          int chunk_elems,
-                                                         const gac_result* __restrict__ res,
-                                                         float beta) {
+                                                         const gac_result* __restrict__ res) {
   constexpr int N = Elem<DT>::kPerVec;
   if (res->nonfinite) return;  // convention: a non-finite step modifies nothing
-  const bool project = res->regime == GAC_PROJECT;
-  const float k = static_cast<float>(res->coef);
+  // g <- scale_g * g + coef_d * d when the step projects and/or clips, else g stays
+  const bool project = res->modified != 0;
+  const float k = static_cast<float>(res->coef_d);
+  const float beta = static_cast<float>(res->scale_g);
   const int tid = threadIdx.x;
 
   struct Tile {
@@ -546,19 +574,19 @@ __global__ __launch_bounds__(T) void apply_kernel(const Seg* __restrict__ segs,
   }
 }
 
-// Pass 2 of the buffer-exchange form: the projected gradient is written over the OLD
+// Pass 2 of the buffer-exchange form: the gradient for the optimizer is written over the OLD
 // reference state (which nobody needs after this step) and g itself is left alone, because
-// the caller hands the g buffers over as the new reference state.  Projection regime:
-// read g, read d, write g' (3 N s bytes); in the other regimes there is nothing to move.
+// the caller hands the g buffers over as the new reference state.  When the step projects
+// (or clips): read g, read d, write g' (3 N s bytes); otherwise there is nothing to move.
 template <int DT, int T, int U>
 __global__ __launch_bounds__(T) void exchange_kernel(const Seg* __restrict__ segs,
                                                             int n_tensors, int64_t n_chunks,
                                                             int chunk_elems,
-                                                            const gac_result* __restrict__ res,
-                                                            float beta) {
+                                                            const gac_result* __restrict__ res) {
   constexpr int N = Elem<DT>::kPerVec;
-  if (res->nonfinite || res->regime != GAC_PROJECT) return;
-  const float k = static_cast<float>(res->coef);
+  if (res->nonfinite || !res->modified) return;
+  const float k = static_cast<float>(res->coef_d);
+  const float beta = static_cast<float>(res->scale_g);
   const int tid = threadIdx.x;
 
   struct Tile {
@@ -758,14 +786,14 @@ __device__ __forceinline__ void adamw_quads(const gchar* ga, gchar* gb, gfloat* 
 template <int DT, int T>
 __global__ __launch_bounds__(T) void apply_adamw_kernel(
     const Seg* __restrict__ segs, const AdamSeg* __restrict__ adam, int n_tensors,
-    int64_t n_chunks, int chunk_elems, const gac_result* __restrict__ res, float beta,
-    AdamScalars h) {
+    int64_t n_chunks, int chunk_elems, const gac_result* __restrict__ res, AdamScalars h) {
   constexpr int Q = GAC_ADAMW_QUADS;
   if (res->nonfinite) return;
   const int regime = res->regime;
-  const bool project = regime == GAC_PROJECT;
+  const bool project = res->modified != 0;  // projected and/or clipped
   const bool skip = regime == GAC_SKIP;
-  const float k = static_cast<float>(res->coef);
+  const float k = static_cast<float>(res->coef_d);
+  const float beta = static_cast<float>(res->scale_g);
   const int tid = threadIdx.x;
   int t = n_tensors - 1;
   for (int64_t cr = blockIdx.x; cr < n_chunks; cr += gridDim.x) {
@@ -801,6 +829,81 @@ __global__ __launch_bounds__(T) void apply_adamw_kernel(
       copy_elem<DT>(ch.a, ch.b, i);
     }
   }
+}
+
+// ------------------------------------------------------------------ alignment statistics
+
+// Table 3 of the paper: the 0.9-quantile and the maximum of |c_t| and the share of steps
+// with |c_t| <= c_low, over recorded steps first_step .. last_step.  One workgroup: the
+// |c_t| go to LDS (missing and non-finite entries as +inf, which sort to the end), a bitonic
+// sort orders them, thread 0 interpolates the quantile at position (m-1) * 0.9.
+__global__ __launch_bounds__(1024) void diag_kernel(const double* __restrict__ hist_c,
+                                                    const int32_t* __restrict__ hist_regime,
+                                                    int hist_cap, int64_t first_step,
+                                                    int64_t last_step, double c_low,
+                                                    gac_diag* __restrict__ out,
+                                                    gac_diag* __restrict__ host_out) {
+  __shared__ double a[kMaxHistory];
+  __shared__ int counts[5];  // safe, projected, skipped, non-finite, |c| <= c_low
+  const int tid = threadIdx.x;
+  if (tid < 5) counts[tid] = 0;
+  __syncthreads();
+  const int64_t n_steps = last_step >= first_step ? last_step - first_step + 1 : 0;
+  const double inf = __longlong_as_double(0x7ff0000000000000LL);
+  for (int i = tid; i < kMaxHistory; i += 1024) {
+    double v = inf;
+    if (i < n_steps) {
+      const int slot = static_cast<int>((first_step + i - 1) % hist_cap);
+      const int regime = hist_regime[slot];
+      if (regime < 0) {
+        atomicAdd(&counts[3], 1);
+      } else {
+        v = fabs(hist_c[slot]);
+        atomicAdd(&counts[regime], 1);
+        if (v <= c_low) atomicAdd(&counts[4], 1);
+      }
+    }
+    a[i] = v;
+  }
+  __syncthreads();
+  for (int size = 2; size <= kMaxHistory; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      for (int i = tid; i < kMaxHistory / 2; i += 1024) {
+        const int lo = 2 * i - (i & (stride - 1));  // index with bit `stride` clear
+        const int hi = lo + stride;
+        const bool ascending = (lo & size) == 0;
+        const double x = a[lo], y = a[hi];
+        if ((x > y) == ascending) {
+          a[lo] = y;
+          a[hi] = x;
+        }
+      }
+      __syncthreads();
+    }
+  }
+  if (tid != 0) return;
+  gac_diag d;
+  d.first_step = first_step;
+  d.last_step = last_step;
+  d.n_nonfinite = counts[3];
+  d.regime_count[0] = counts[0];
+  d.regime_count[1] = counts[1];
+  d.regime_count[2] = counts[2];
+  const int m = counts[0] + counts[1] + counts[2];
+  d.n_values = m;
+  d.q90_abs_c = 0.0;
+  d.max_abs_c = 0.0;
+  d.frac_le_c_low = 0.0;
+  if (m > 0) {
+    const double pos = (static_cast<double>(m) - 1.0) * 0.9;
+    const int lo = static_cast<int>(floor(pos));
+    const int hi = lo + 1 < m ? lo + 1 : m - 1;
+    d.q90_abs_c = a[lo] + (a[hi] - a[lo]) * (pos - static_cast<double>(lo));
+    d.max_abs_c = a[m - 1];
+    d.frac_le_c_low = static_cast<double>(counts[4]) / static_cast<double>(m);
+  }
+  *out = d;
+  if (host_out != nullptr) *host_out = d;
 }
 
 // ------------------------------------------------------------------ state maintenance
@@ -875,42 +978,50 @@ hipError_t launch_finalize(const double* dev_partials, int n_partials, const dou
 }
 
 hipError_t launch_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
-                        int chunk_elems, const gac_result* dev_result, float beta, int grid,
+                        int chunk_elems, const gac_result* dev_result, int grid,
                         hipStream_t stream) {
   if (dtype == GAC_F32) {
     apply_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, beta);
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result);
   } else {
     apply_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, beta);
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_exchange(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
-                           int chunk_elems, const gac_result* dev_result, float beta, int grid,
+                           int chunk_elems, const gac_result* dev_result, int grid,
                            hipStream_t stream) {
   if (dtype == GAC_F32) {
     exchange_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, beta);
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result);
   } else {
     exchange_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, beta);
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_apply_adamw(int dtype, const Seg* dev_segs, const AdamSeg* dev_adam,
                               int n_tensors, int64_t n_chunks, int chunk_elems,
-                              const gac_result* dev_result, float beta, AdamScalars h, int grid,
+                              const gac_result* dev_result, AdamScalars h, int grid,
                               hipStream_t stream) {
   if (dtype == GAC_F32) {
     apply_adamw_kernel<GAC_F32, GAC_ADAMW_THREADS><<<grid, GAC_ADAMW_THREADS, 0, stream>>>(
-        dev_segs, dev_adam, n_tensors, n_chunks, chunk_elems, dev_result, beta, h);
+        dev_segs, dev_adam, n_tensors, n_chunks, chunk_elems, dev_result, h);
   } else {
     apply_adamw_kernel<GAC_BF16, GAC_ADAMW_THREADS><<<grid, GAC_ADAMW_THREADS, 0, stream>>>(
-        dev_segs, dev_adam, n_tensors, n_chunks, chunk_elems, dev_result, beta, h);
+        dev_segs, dev_adam, n_tensors, n_chunks, chunk_elems, dev_result, h);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_diag(const double* hist_c, const int32_t* hist_regime, int hist_cap,
+                       int64_t first_step, int64_t last_step, double c_low, gac_diag* dev_out,
+                       gac_diag* host_out, hipStream_t stream) {
+  diag_kernel<<<1, 1024, 0, stream>>>(hist_c, hist_regime, hist_cap, first_step, last_step, c_low,
+                                      dev_out, host_out);
   return hipGetLastError();
 }
 

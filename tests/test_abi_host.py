@@ -22,16 +22,17 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     L = B.lib()
     names = declared_functions()
-    assert len(names) >= 18 and "gac_init" in names and "gac_step" in names
+    assert len(names) >= 21 and "gac_init" in names and "gac_step" in names
     for n in names:
         assert hasattr(L, n), f"libgac.so does not export {n}"
     assert B.lib().gac_version().decode().startswith("gac-mi355x")
 
 
 def test_struct_layouts_match_header():
-    assert ctypes.sizeof(B.GacResult) == 64
+    assert ctypes.sizeof(B.GacResult) == 104
+    assert ctypes.sizeof(B.GacDiag) == 80
     assert ctypes.sizeof(B.GacAdamWHyper) == 48
-    assert ctypes.sizeof(B.GacConfig) == 80
+    assert ctypes.sizeof(B.GacConfig) == 96
 
 
 def test_default_config_is_the_papers():
@@ -51,7 +52,7 @@ def test_bad_thresholds_are_rejected_before_any_gpu_call(c_low, c_high):
 
 
 def test_bad_arguments():
-    for kwargs in (dict(eps=-1.0), dict(beta=-0.5)):
+    for kwargs in (dict(eps=-1.0), dict(beta=-0.5), dict(max_grad_norm=-1.0)):
         with pytest.raises(B.GacError) as e:
             B.Gac([16], B.F32, **kwargs)
         assert e.value.code == B.ERR_BAD_THRESHOLDS

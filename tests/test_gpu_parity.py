@@ -222,7 +222,7 @@ def test_async_step_and_device_result():
     rec = B.GacResult()
     hip = ctypes.CDLL("libamdhip64.so")
     hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
-    assert hip.hipMemcpy(ctypes.byref(rec), ctx.gac_result_device(), 64, 2) == 0  # device -> host
+    assert hip.hipMemcpy(ctypes.byref(rec), ctx.gac_result_device(), ctypes.sizeof(rec), 2) == 0  # device -> host
     assert (rec.c, rec.regime, rec.coef) == (res.c, res.regime, res.coef) and rec.step == 1
 
 
