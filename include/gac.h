@@ -23,9 +23,8 @@
  *     example PyTorch tensors); every other pointer is host memory.  Pointer
  *     LISTS (grad_ptrs, state_ptrs, ...) are host arrays of device pointers,
  *     one entry per tensor, copied during the call.
- *   - Tensors are contiguous, element-aligned; 16-byte aligned tensors take the
- *     fast path, others a slower element-wise path with identical results up to
- *     summation order.  numel may be 0.
+ *   - Tensors are contiguous and element-aligned; no further alignment is needed (views
+ *     that start anywhere inside a flat buffer take the same vector path).  numel may be 0.
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
  *     All work is enqueued on it.  A context is not thread-safe and its calls
  *     must be issued in stream order.

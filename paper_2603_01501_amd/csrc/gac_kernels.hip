@@ -31,7 +31,13 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // Pointers read from the tensor table are generic; casting them to the global address
 // space lets the compiler emit global_load/global_store instead of flat accesses.
 #define GAC_GLOBAL __attribute__((address_space(1)))
-typedef GAC_GLOBAL u32x4 gvec;
+// Tensors are only guaranteed element alignment (views into flat parameter buffers start
+// anywhere), so the 16- and 8-byte accesses are declared with 2-byte alignment.  The target
+// supports unaligned vector memory accesses, so the compiler still emits one
+// global_load_dwordx4 / dwordx2 per access; aligned tensors lose nothing.
+typedef u32x4 u32x4_ua __attribute__((aligned(2)));
+typedef u32x2 u32x2_ua __attribute__((aligned(2)));
+typedef GAC_GLOBAL u32x4_ua gvec;
 typedef GAC_GLOBAL char gchar;
 typedef GAC_GLOBAL float gfloat;
 typedef GAC_GLOBAL uint32_t gu32;
@@ -202,10 +208,6 @@ __device__ __forceinline__ Chunk locate(const Seg* __restrict__ segs, int& t, in
   return ch;
 }
 
-__device__ __forceinline__ bool aligned16(const GAC_GLOBAL void* p) {
-  return ((uintptr_t)(p) & 15u) == 0;
-}
-
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -283,7 +285,7 @@ __global__ __launch_bounds__(T) void reduce_kernel(const Seg* __restrict__ segs,
     c += gridDim.x;
     more = c < n_chunks;
     if (more) next = locate<false>(segs, t, c, chunk_elems, Elem<DT>::kSize);
-    if (aligned16(ch.a) && aligned16(ch.b)) {
+    {
       const gvec* __restrict__ gv = reinterpret_cast<const gvec*>(ch.a);
       const gvec* __restrict__ dv = reinterpret_cast<const gvec*>(ch.b);
       const int nvec = ch.len / N;
@@ -320,15 +322,6 @@ __global__ __launch_bounds__(T) void reduce_kernel(const Seg* __restrict__ segs,
         acc[0] += static_cast<double>(x * y);
         acc[1] += static_cast<double>(x * x);
         acc[2] += static_cast<double>(y * y);
-      }
-    } else {
-      // element-wise path for tensors that are not 16-byte aligned
-      for (int i = tid; i < ch.len; i += T) {
-        const double x = static_cast<double>(load_elem<DT>(ch.a, i));
-        const double y = static_cast<double>(load_elem<DT>(ch.b, i));
-        acc[0] = fma(x, y, acc[0]);
-        acc[1] = fma(x, x, acc[1]);
-        acc[2] = fma(y, y, acc[2]);
       }
     }
   }
@@ -447,45 +440,32 @@ __device__ __forceinline__ u32x4 project_vec(u32x4 a, u32x4 b, float k, float be
   return pack<DT>(x);
 }
 
-// The part of a chunk that is not handled by the whole-tile fast path: any length, any
-// element alignment.
+// A chunk that is not a whole tile (the tail of a tensor, or a non-default chunk size).
 template <int DT, int T, int U>
 __device__ __forceinline__ void apply_chunk_generic(const Chunk& ch, bool project, float k,
                                                     float beta) {
   constexpr int N = Elem<DT>::kPerVec;
   const int tid = threadIdx.x;
   gchar* ga = const_cast<gchar*>(ch.a);
-  if (aligned16(ch.a) && aligned16(ch.b)) {
-    gvec* gv = reinterpret_cast<gvec*>(ga);
-    gvec* dv = reinterpret_cast<gvec*>(ch.b);
-    const int nvec = ch.len / N;
-    if (project) {
-      for (int i = tid; i < nvec; i += T) {
-        const u32x4 a = ld16<GAC_APPLY_NT_LOAD>(gv + i), b = ld16<GAC_APPLY_NT_LOAD>(dv + i);
-        st16<GAC_APPLY_NT_STORE>(gv + i, project_vec<DT>(a, b, k, beta));
-        st16<GAC_APPLY_NT_STORE>(dv + i, a);
-      }
-      const int e = nvec * N + tid;  // at most N-1 leftover elements
-      if (e < ch.len) {
-        const float x = load_elem<DT>(ch.a, e), y = load_elem<DT>(ch.b, e);
-        copy_elem<DT>(ch.a, ch.b, e);
-        store_elem<DT>(ga, e, fmaf(k, y, beta * x));
-      }
-    } else {
-      for (int i = tid; i < nvec; i += T) st16<GAC_APPLY_NT_STORE>(dv + i, ld16<GAC_APPLY_NT_LOAD>(gv + i));
-      const int e = nvec * N + tid;
-      if (e < ch.len) copy_elem<DT>(ch.a, ch.b, e);
+  gvec* gv = reinterpret_cast<gvec*>(ga);
+  gvec* dv = reinterpret_cast<gvec*>(ch.b);
+  const int nvec = ch.len / N;
+  if (project) {
+    for (int i = tid; i < nvec; i += T) {
+      const u32x4 a = ld16<GAC_APPLY_NT_LOAD>(gv + i), b = ld16<GAC_APPLY_NT_LOAD>(dv + i);
+      st16<GAC_APPLY_NT_STORE>(gv + i, project_vec<DT>(a, b, k, beta));
+      st16<GAC_APPLY_NT_STORE>(dv + i, a);
+    }
+    const int e = nvec * N + tid;  // at most N-1 leftover elements
+    if (e < ch.len) {
+      const float x = load_elem<DT>(ch.a, e), y = load_elem<DT>(ch.b, e);
+      copy_elem<DT>(ch.a, ch.b, e);
+      store_elem<DT>(ga, e, fmaf(k, y, beta * x));
     }
   } else {
-    for (int i = tid; i < ch.len; i += T) {
-      if (project) {
-        const float x = load_elem<DT>(ch.a, i), y = load_elem<DT>(ch.b, i);
-        copy_elem<DT>(ch.a, ch.b, i);
-        store_elem<DT>(ga, i, fmaf(k, y, beta * x));
-      } else {
-        copy_elem<DT>(ch.a, ch.b, i);
-      }
-    }
+    for (int i = tid; i < nvec; i += T) st16<GAC_APPLY_NT_STORE>(dv + i, ld16<GAC_APPLY_NT_LOAD>(gv + i));
+    const int e = nvec * N + tid;
+    if (e < ch.len) copy_elem<DT>(ch.a, ch.b, e);
   }
 }
 
@@ -494,8 +474,7 @@ __device__ __forceinline__ void apply_chunk_generic(const Chunk& ch, bool projec
 // vectors of g and of d in registers, so the whole chunk is read before any of it is
 // written, and the loads of the workgroup's NEXT whole tile are issued before the current
 // one is computed and stored (two register tiles), which keeps reads in flight during the
-// arithmetic and the stores.  Other chunks (tensor tails, unaligned tensors) take the
-// generic path.
+// arithmetic and the stores.  Other chunks (tensor tails) take the generic path.
 //
 // Chunks are walked from the end of the list towards its start: the reduction pass has
 // just streamed the list front to back, so its last chunks are the ones most likely to
@@ -517,7 +496,7 @@ __global__ __launch_bounds__(T) void apply_kernel(const Seg* __restrict__ segs,
     u32x4 a[U], b[U];
   };
   auto whole = [&](const Chunk& ch) {
-    return ch.len == T * U * N && aligned16(ch.a) && aligned16(ch.b);
+    return ch.len == T * U * N;
   };
   auto load_tile = [&](const Chunk& ch, Tile& tl) {
     const gvec* gv = reinterpret_cast<const gvec*>(ch.a) + tid;
@@ -593,7 +572,7 @@ __global__ __launch_bounds__(T) void exchange_kernel(const Seg* __restrict__ seg
     u32x4 a[U], b[U];
   };
   auto whole = [&](const Chunk& ch) {
-    return ch.len == T * U * N && aligned16(ch.a) && aligned16(ch.b);
+    return ch.len == T * U * N;
   };
   auto load_tile = [&](const Chunk& ch, Tile& tl) {
     const gvec* gv = reinterpret_cast<const gvec*>(ch.a) + tid;
@@ -610,17 +589,13 @@ __global__ __launch_bounds__(T) void exchange_kernel(const Seg* __restrict__ seg
       st16<GAC_APPLY_NT_STORE>(dv + u * T, project_vec<DT>(tl.a[u], tl.b[u], k, beta));
   };
   auto generic = [&](const Chunk& ch) {
-    int first_scalar = 0;
-    if (aligned16(ch.a) && aligned16(ch.b)) {
-      const gvec* gv = reinterpret_cast<const gvec*>(ch.a);
-      gvec* dv = reinterpret_cast<gvec*>(ch.b);
-      const int nvec = ch.len / N;
-      for (int i = tid; i < nvec; i += T)
-        st16<GAC_APPLY_NT_STORE>(dv + i, project_vec<DT>(ld16<GAC_APPLY_NT_LOAD>(gv + i),
-                                                         ld16<GAC_APPLY_NT_LOAD>(dv + i), k, beta));
-      first_scalar = nvec * N;
-    }
-    for (int i = first_scalar + tid; i < ch.len; i += T)
+    const gvec* gv = reinterpret_cast<const gvec*>(ch.a);
+    gvec* dv = reinterpret_cast<gvec*>(ch.b);
+    const int nvec = ch.len / N;
+    for (int i = tid; i < nvec; i += T)
+      st16<GAC_APPLY_NT_STORE>(dv + i, project_vec<DT>(ld16<GAC_APPLY_NT_LOAD>(gv + i),
+                                                       ld16<GAC_APPLY_NT_LOAD>(dv + i), k, beta));
+    for (int i = nvec * N + tid; i < ch.len; i += T)
       store_elem<DT>(ch.b, i, fmaf(k, load_elem<DT>(ch.b, i), beta * load_elem<DT>(ch.a, i)));
   };
 
@@ -674,9 +649,11 @@ __device__ __forceinline__ void adamw_elem(float g, float& p, float& m, float& v
 template <int DT> struct Quad;
 template <> struct Quad<GAC_F32> {
   typedef u32x4 type;
+  typedef u32x4_ua stored;  // the same bytes, declared with element alignment only
 };
 template <> struct Quad<GAC_BF16> {
   typedef u32x2 type;
+  typedef u32x2_ua stored;
 };
 
 template <int DT>
@@ -716,7 +693,7 @@ __device__ __forceinline__ void adamw_quads(const gchar* ga, gchar* gb, gfloat* 
                                             bool project, bool skip, float k, float beta,
                                             const AdamScalars& h) {
   typedef typename Quad<DT>::type quad_t;
-  typedef GAC_GLOBAL quad_t gquad;
+  typedef GAC_GLOBAL typename Quad<DT>::stored gquad;
   const gquad* gq = reinterpret_cast<const gquad*>(ga);
   gquad* dq = reinterpret_cast<gquad*>(gb);
   gvec* vp = reinterpret_cast<gvec*>(pp);
@@ -803,18 +780,13 @@ __global__ __launch_bounds__(T) void apply_adamw_kernel(
     gfloat* pm = (gfloat*)(as.m) + ch.elem_off;
     gfloat* pv = (gfloat*)(as.v) + ch.elem_off;
     gchar* pl = as.p_lowp ? (gchar*)(as.p_lowp) + ch.elem_off * Elem<DT>::kSize : nullptr;
-    const bool vec_ok = aligned16(ch.a) && aligned16(ch.b) && aligned16(pp) && aligned16(pm) &&
-                        aligned16(pv) && aligned16(pl);
-    int first_scalar = 0;
-    if (vec_ok) {
-      const int nquad = ch.len / 4;
-      int j = tid;
-      for (; j + (Q - 1) * T < nquad; j += Q * T)
-        adamw_quads<DT, Q, GAC_ADAMW_NT_LOAD>(ch.a, ch.b, pp, pm, pv, pl, j, T, project, skip, k, beta, h);
-      for (; j < nquad; j += T)
-        adamw_quads<DT, 1, GAC_ADAMW_NT_LOAD>(ch.a, ch.b, pp, pm, pv, pl, j, T, project, skip, k, beta, h);
-      first_scalar = nquad * 4;
-    }
+    const int nquad = ch.len / 4;
+    int j = tid;
+    for (; j + (Q - 1) * T < nquad; j += Q * T)
+      adamw_quads<DT, Q, GAC_ADAMW_NT_LOAD>(ch.a, ch.b, pp, pm, pv, pl, j, T, project, skip, k, beta, h);
+    for (; j < nquad; j += T)
+      adamw_quads<DT, 1, GAC_ADAMW_NT_LOAD>(ch.a, ch.b, pp, pm, pv, pl, j, T, project, skip, k, beta, h);
+    const int first_scalar = nquad * 4;
     for (int i = first_scalar + tid; i < ch.len; i += T) {
       if (!skip) {
         float g = load_elem<DT>(ch.a, i);
@@ -918,16 +890,12 @@ __global__ __launch_bounds__(kThreads) void state_kernel(const Seg* __restrict__
   int t = 0;
   for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
     const Chunk ch = locate<false>(segs, t, c, chunk_elems, Elem<DT>::kSize);
-    const bool vec_ok = aligned16(ch.b) && (op == kStateZero || aligned16(ch.a));
-    int first_scalar = 0;
-    if (vec_ok) {
-      const gvec* src = reinterpret_cast<const gvec*>(ch.a);
-      gvec* dst = reinterpret_cast<gvec*>(ch.b);
-      const int nvec = ch.len / N;
-      const u32x4 zero = {0u, 0u, 0u, 0u};
-      for (int i = tid; i < nvec; i += kThreads) dst[i] = (op == kStateZero) ? zero : src[i];
-      first_scalar = nvec * N;
-    }
+    const gvec* src = reinterpret_cast<const gvec*>(ch.a);
+    gvec* dst = reinterpret_cast<gvec*>(ch.b);
+    const int nvec = ch.len / N;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    for (int i = tid; i < nvec; i += kThreads) dst[i] = (op == kStateZero) ? zero : src[i];
+    const int first_scalar = nvec * N;
     for (int i = first_scalar + tid; i < ch.len; i += kThreads) {
       if (op == kStateZero) {
         if constexpr (DT == GAC_F32) {
