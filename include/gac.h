@@ -144,8 +144,13 @@ void gac_destroy(gac_ctx* ctx);
 /* One whole update (steps 1-5 above) on one GPU.
  *   grad_ptrs  host list of n_tensors device pointers to g (modified in place only in the
  *              projection regime).  May differ from call to call; sizes may not.
- *   host_out   NULL: fully asynchronous.  Otherwise the call waits for the stream and
- *              fills *host_out; the caller skips its optimizer step if regime is GAC_SKIP.
+ *   host_out   NULL: fully asynchronous.  Otherwise the call waits until the regime is known
+ *              (pass 2 may still be running) and fills *host_out; the caller skips its
+ *              optimizer step if regime is GAC_SKIP.
+ * With host_out == NULL and the same pointers as in the previous call, the call only launches
+ * kernels (no copy, no host wait, no memset), so it can be captured into a HIP graph and
+ * replayed: the step counter and the record of c_t live on the device and keep counting.
+ * Thresholds and max_grad_norm are launch arguments and are frozen into a captured graph.
  * The state d becomes the raw g in all three regimes.  If a sum is not finite (a
  * convention of this library, the paper does not cover it): nonfinite = 1, regime =
  * GAC_SKIP, neither g nor d is touched, and the return value is GAC_ERR_NONFINITE when

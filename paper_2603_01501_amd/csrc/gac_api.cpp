@@ -77,7 +77,7 @@ struct gac_ctx {
   int grid_adamw = 1;  // workgroups of the fused AdamW apply kernel
   double c_low = 0, c_high = 0, eps = 0, beta = 1;
   double max_grad_norm = 0;
-  int64_t step = 0;
+  int64_t* dev_step = nullptr;  // the step counter lives on the device (see DecideParams)
 
   // record of (c_t, regime) per step: a ring on the device, written by the finalize kernel
   double* hist_c = nullptr;
@@ -238,6 +238,13 @@ int wait_result(gac_ctx* ctx, gac_result* host_out) {
   return host_out->nonfinite ? GAC_ERR_NONFINITE : GAC_OK;
 }
 
+// Reads the device-side step counter (waits for the stream's work first).
+int read_step(gac_ctx* ctx, hipStream_t stream, int64_t* out) {
+  GAC_HIP(ctx, hipStreamSynchronize(stream));
+  GAC_HIP(ctx, hipMemcpy(out, ctx->dev_step, sizeof(int64_t), hipMemcpyDeviceToHost));
+  return GAC_OK;
+}
+
 DecideParams decide_params(const gac_ctx* ctx) {
   DecideParams p;
   p.c_low = ctx->c_low;
@@ -245,7 +252,7 @@ DecideParams decide_params(const gac_ctx* ctx) {
   p.eps = ctx->eps;
   p.beta = ctx->beta;
   p.max_grad_norm = ctx->max_grad_norm;
-  p.step = ctx->step;
+  p.step = ctx->dev_step;
   p.hist_c = ctx->hist_c;
   p.hist_regime = ctx->hist_regime;
   p.hist_cap = ctx->hist_cap;
@@ -267,7 +274,6 @@ int run_step(gac_ctx* ctx, void* const* grad_ptrs, bool do_reduce, const double*
              ApplyKind kind, const AdamScalars* adam, hipStream_t stream, gac_result* host_out) {
   int rc = upload_segs(ctx, const_cast<const void* const*>(grad_ptrs), ctx->state.data(), stream);
   if (rc != GAC_OK) return rc;
-  ctx->step += 1;
   StepEvents* ev = next_events(ctx);
   if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[0], stream));
   int mode = 2;
@@ -438,6 +444,8 @@ int gac_init(gac_ctx** out, const gac_config* cfg) {
                                        ctx->pinned_result, 0));
   GAC_HIP(ctx, hipEventCreateWithFlags(&ctx->result_event, hipEventDisableTiming));
   std::memset(ctx->pinned_result, 0, sizeof(gac_result));
+  GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_step), sizeof(int64_t)));
+  GAC_HIP(ctx, gac::launch_set_step(ctx->dev_step, 0, nullptr));
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->hist_c), sizeof(double) * ctx->hist_cap));
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->hist_regime), sizeof(int32_t) * ctx->hist_cap));
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_diag), sizeof(gac_diag)));
@@ -466,6 +474,7 @@ void gac_destroy(gac_ctx* ctx) {
     if (ctx->dev_sums) (void)hipFree(ctx->dev_sums);
     if (ctx->dev_result) (void)hipFree(ctx->dev_result);
     if (ctx->pinned_result) (void)hipHostFree(ctx->pinned_result);
+    if (ctx->dev_step) (void)hipFree(ctx->dev_step);
     if (ctx->hist_c) (void)hipFree(ctx->hist_c);
     if (ctx->hist_regime) (void)hipFree(ctx->hist_regime);
     if (ctx->dev_diag) (void)hipFree(ctx->dev_diag);
@@ -584,7 +593,10 @@ int gac_state_export(gac_ctx* ctx, void* const* dst_ptrs, int64_t* step_out, voi
   int rc = check_ptrs(ctx, const_cast<const void* const*>(dst_ptrs));
   if (rc != GAC_OK) return rc;
   DeviceGuard guard(ctx->device);
-  if (step_out) *step_out = ctx->step;
+  if (step_out) {
+    rc = read_step(ctx, static_cast<hipStream_t>(hip_stream), step_out);
+    if (rc != GAC_OK) return rc;
+  }
   return state_op(ctx, gac::kStateCopy, const_cast<const void* const*>(ctx->state.data()), dst_ptrs,
                   static_cast<hipStream_t>(hip_stream));
 }
@@ -597,7 +609,7 @@ int gac_state_import(gac_ctx* ctx, void* const* src_ptrs, int64_t step, void* hi
   rc = state_op(ctx, gac::kStateCopy, const_cast<const void* const*>(src_ptrs), ctx->state.data(),
                 static_cast<hipStream_t>(hip_stream));
   if (rc == GAC_OK) {
-    ctx->step = step;
+    GAC_HIP(ctx, gac::launch_set_step(ctx->dev_step, step, static_cast<hipStream_t>(hip_stream)));
     ctx->hist_first = step + 1;
   }
   return rc;
@@ -608,7 +620,7 @@ int gac_reset(gac_ctx* ctx, void* hip_stream) {
   DeviceGuard guard(ctx->device);
   int rc = state_op(ctx, gac::kStateZero, nullptr, ctx->state.data(), static_cast<hipStream_t>(hip_stream));
   if (rc == GAC_OK) {
-    ctx->step = 0;
+    GAC_HIP(ctx, gac::launch_set_step(ctx->dev_step, 0, static_cast<hipStream_t>(hip_stream)));
     ctx->hist_first = 1;
   }
   return rc;
@@ -624,11 +636,15 @@ int gac_set_thresholds(gac_ctx* ctx, double c_low, double c_high) {
 
 namespace {
 // Range of step numbers whose record is still in the ring.
-void recorded_range(const gac_ctx* ctx, int64_t* first, int64_t* last) {
-  *last = ctx->step;
-  int64_t f = ctx->step - ctx->hist_cap + 1;
+int recorded_range(gac_ctx* ctx, hipStream_t stream, int64_t* first, int64_t* last) {
+  int64_t step = 0;
+  int rc = read_step(ctx, stream, &step);
+  if (rc != GAC_OK) return rc;
+  *last = step;
+  int64_t f = step - ctx->hist_cap + 1;
   if (f < ctx->hist_first) f = ctx->hist_first;
   *first = f;
+  return GAC_OK;
 }
 }  // namespace
 
@@ -638,7 +654,8 @@ int gac_history_read(gac_ctx* ctx, int64_t max_n, double* c_out, int32_t* regime
   DeviceGuard guard(ctx->device);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   int64_t first, last;
-  recorded_range(ctx, &first, &last);
+  int rc = recorded_range(ctx, stream, &first, &last);
+  if (rc != GAC_OK) return rc;
   int64_t n = last >= first ? last - first + 1 : 0;
   if (n > max_n) {
     first += n - max_n;
@@ -647,7 +664,6 @@ int gac_history_read(gac_ctx* ctx, int64_t max_n, double* c_out, int32_t* regime
   *n_out = n;
   if (first_step_out) *first_step_out = first;
   if (n == 0) return GAC_OK;
-  GAC_HIP(ctx, hipStreamSynchronize(stream));
   std::vector<double> c(ctx->hist_cap);
   std::vector<int32_t> r(ctx->hist_cap);
   GAC_HIP(ctx, hipMemcpy(c.data(), ctx->hist_c, sizeof(double) * ctx->hist_cap, hipMemcpyDeviceToHost));
@@ -665,7 +681,8 @@ int gac_diag_summary(gac_ctx* ctx, int64_t burn_in, gac_diag* out, void* hip_str
   DeviceGuard guard(ctx->device);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   int64_t first, last;
-  recorded_range(ctx, &first, &last);
+  int rc = recorded_range(ctx, stream, &first, &last);
+  if (rc != GAC_OK) return rc;
   if (first < burn_in + 1) first = burn_in + 1;
   GAC_HIP(ctx, gac::launch_diag(ctx->hist_c, ctx->hist_regime, ctx->hist_cap, first, last, ctx->c_low,
                                 ctx->dev_diag, ctx->pinned_diag_dev, stream));

@@ -33,7 +33,8 @@ static_assert(sizeof(AdamSeg) == 32, "AdamSeg layout is shared with device code"
 struct DecideParams {
   double c_low, c_high, eps, beta;
   double max_grad_norm;  // 0 = no clipping
-  int64_t step;
+  int64_t* step;         // device-side step counter, incremented by the finalize kernel, so that
+                         // a captured and replayed launch sequence keeps counting
   double* hist_c;        // ring of recorded cosines, hist_cap entries (or null)
   int32_t* hist_regime;  // ring of recorded regimes
   int32_t hist_cap;
@@ -89,6 +90,10 @@ hipError_t launch_apply_adamw(int dtype, const Seg* dev_segs, const AdamSeg* dev
                               int n_tensors, int64_t n_chunks, int chunk_elems,
                               const gac_result* dev_result, AdamScalars h, int grid,
                               hipStream_t stream);
+
+// Sets the device-side step counter (init / reset / import); a one-thread kernel rather than
+// a memset so that it can sit in a captured graph.
+hipError_t launch_set_step(int64_t* dev_step, int64_t value, hipStream_t stream);
 
 hipError_t launch_state_op(int dtype, int op, const Seg* dev_segs, int64_t n_chunks,
                            int chunk_elems, int grid, hipStream_t stream);

@@ -365,6 +365,8 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const double* __rest
   }
   if (!(mode & 2)) return;
   const double s_gd = s[0], s_gg = s[1], s_dd = s[2];
+  const int64_t step = *p.step + 1;  // only this thread of this one-workgroup kernel touches it
+  *p.step = step;
   gac_result r;
   r.dot = s_gd;
   r.gg = s_gg;
@@ -378,7 +380,7 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const double* __rest
   r.nonfinite = 0;
   r.modified = 0;
   r.reserved = 0;
-  r.step = p.step;
+  r.step = step;
   if (!(isfinite(s_gd) && isfinite(s_gg) && isfinite(s_dd))) {
     r.c = __longlong_as_double(0x7ff8000000000000LL);
     r.regime = GAC_SKIP;
@@ -417,7 +419,7 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const double* __rest
     }
   }
   if (p.hist_c != nullptr) {
-    const int slot = static_cast<int>((p.step - 1) % p.hist_cap);
+    const int slot = static_cast<int>((step - 1) % p.hist_cap);
     p.hist_c[slot] = r.c;
     p.hist_regime[slot] = r.nonfinite ? -1 : r.regime;
   }
@@ -990,6 +992,15 @@ hipError_t launch_diag(const double* hist_c, const int32_t* hist_regime, int his
                        gac_diag* host_out, hipStream_t stream) {
   diag_kernel<<<1, 1024, 0, stream>>>(hist_c, hist_regime, hist_cap, first_step, last_step, c_low,
                                       dev_out, host_out);
+  return hipGetLastError();
+}
+
+namespace {
+__global__ void set_step_kernel(int64_t* dev_step, int64_t value) { *dev_step = value; }
+}  // namespace
+
+hipError_t launch_set_step(int64_t* dev_step, int64_t value, hipStream_t stream) {
+  set_step_kernel<<<1, 1, 0, stream>>>(dev_step, value);
   return hipGetLastError();
 }
 

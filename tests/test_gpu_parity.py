@@ -389,3 +389,50 @@ def test_exchange_form_argument_checks():
     before = arr[0]
     assert B.lib().gac_step_exchange(ctx2._ctx, arr, None, ctypes.byref(res)) == B.ERR_NONFINITE
     assert arr[0] == before and res.nonfinite == 1  # no buffer changed hands
+
+
+# ------------------------------------------------------------------ HIP graph capture
+
+def test_async_step_replayed_from_a_hip_graph():
+    """The asynchronous step is three kernel launches; captured once and replayed, every
+    replay (with eager work and synchronisations in between) must equal the eager step on
+    the same inputs, and the device-side step counter and record must keep counting."""
+    dtype = torch.bfloat16
+    shapes = [(70000,), (33,), (4096,), (9001,)]
+    numel = [W.numel(s) for s in shapes]
+    stream_a = W.AR1Stream(shapes, dtype, 0.2, 1e-3, config_id=25, device=DEV)
+    g = [torch.empty(s, dtype=dtype, device=DEV) for s in shapes]
+    d = [torch.zeros(s, dtype=dtype, device=DEV) for s in shapes]
+    ctx = new_ctx(shapes, dtype, state=d)
+    ref = new_ctx(shapes, dtype)
+    stream_a.next_into(g)
+    # one eager call first: it uploads the pointer table, which a capture cannot do
+    ctx.gac_step(g, sync=False)
+    ref.gac_step(U.clone_list(g))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    stream_a.next_into(g)
+    g_in = U.clone_list(g)
+    with torch.cuda.graph(graph, stream=side):
+        ctx.gac_step(g, stream=torch.cuda.current_stream(), sync=False)
+    # capture does not run anything: the state still holds the first gradient
+    seen = []
+    for i in range(5):
+        if i:
+            stream_a.next_into(g)
+            g_in = U.clone_list(g)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        g_ref = U.clone_list(g_in)
+        r = ref.gac_step(g_ref)
+        torch.cuda.synchronize()
+        assert all(U.bits_equal(a, b) for a, b in zip(g, g_ref)), f"replay {i}"
+        assert all(U.bits_equal(a, b) for a, b in zip(d, g_in)), f"replay {i}: state"
+        seen.append((r.c, r.regime))
+        _ = sum(float(t.float().sum()) for t in g)  # eager work between replays
+    c_hist, r_hist, first = ctx.gac_history_read()
+    assert first == 1 and len(c_hist) == 6
+    assert list(zip(c_hist[1:], r_hist[1:])) == seen
+    assert B.PROJECT in r_hist
