@@ -41,5 +41,25 @@ def build(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+C_CHECK_SRC = os.path.join(_ROOT, "tests", "c_abi_check.cpp")
+C_CHECK_BIN = os.path.join(_ROOT, "tests", "c_abi_check.bin")
+
+
+def build_c_abi_check(verbose: bool = False) -> str:
+    """A plain C++ program that calls libgac.so without Python or PyTorch (used by a GPU test)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-O2", "-std=c++17", "-Wall", "-Wno-unused-command-line-argument",
+           "-I", os.path.join(_ROOT, "include"), C_CHECK_SRC, "-o", C_CHECK_BIN,
+           "-L", _PKG, "-l:libgac.so", "-Wl,-rpath," + _PKG, "-Wl,-rpath,$ORIGIN/../paper_2603_01501_amd"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        sys.stderr.write(r.stdout + r.stderr)
+        raise RuntimeError("hipcc failed building tests/c_abi_check.bin")
+    return C_CHECK_BIN
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_c_abi_check(verbose=True))

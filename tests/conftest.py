@@ -15,7 +15,7 @@ def pytest_configure(config):
 def pytest_collection_modifyitems(config, items):
     """A plain `pytest tests/` on a box without a GPU skips the GPU tests.  When the
     GPU tests were asked for by name (`-m gpu`) they are never skipped: without a
-    device they then fail, so a broken GPU machine cannot read as green."""
+    device they then fail, so a machine whose GPU is not visible cannot read as green."""
     markexpr = (config.getoption("markexpr") or "").strip()
     if markexpr == "gpu":
         return
