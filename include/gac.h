@@ -226,6 +226,20 @@ int gac_history_read(gac_ctx* ctx, int64_t max_n, double* c_out, int32_t* regime
  * > burn_in.  One small kernel on the stream; waits for it. */
 int gac_diag_summary(gac_ctx* ctx, int64_t burn_in, gac_diag* out, void* hip_stream);
 
+/* Threshold sweep over the record (the paper's Table 4 varies (c_low, c_high) around the
+ * defaults; Section 4.2 gives the rule).  c_t is computed from the raw gradients before any
+ * intervention (Appendix A.1), so on a given gradient sequence it does not depend on the
+ * thresholds in force, and the regimes that any other pair would have chosen can be counted
+ * from the record: for each pair i, counts[3*i + r] receives the number of recorded finite
+ * steps with step number > burn_in that the pair (c_low[i], c_high[i]) puts in regime r
+ * (GAC_SAFE, GAC_PROJECT, GAC_SKIP).  It says nothing about how training would have moved
+ * under those thresholds.  c_low, c_high, counts: host arrays; 1 <= n_pairs <=
+ * GAC_MAX_SWEEP_PAIRS; every pair must satisfy 0 < c_low < c_high (else
+ * GAC_ERR_BAD_THRESHOLDS, nothing written).  One small kernel on the stream; waits for it. */
+#define GAC_MAX_SWEEP_PAIRS 64
+int gac_threshold_sweep(gac_ctx* ctx, int64_t burn_in, int32_t n_pairs, const double* c_low,
+                        const double* c_high, int32_t* counts, void* hip_stream);
+
 /* Host-only planning query (no GPU call): the number of work items the tensor list is cut
  * into (no item straddles two tensors) and the total element count.  chunk_elems = 0 uses
  * the default for the dtype. */

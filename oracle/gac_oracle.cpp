@@ -272,4 +272,21 @@ void gac_oracle_alignment_stats(const double* c, int64_t n, int64_t burn_in, dou
   out[2] = static_cast<double>(inside) / static_cast<double>(a.size());
 }
 
+// Regime counts of a run's cosines c_1 .. c_n under a threshold pair: the rule of
+// Section 4.2 (safe if |c| <= c_low, violation if |c| >= c_high, projection between) applied
+// to every c_t after the first `burn_in` updates; NaN entries (non-finite steps) are left
+// out.  counts = {safe, projected, skipped}.  Table 4 varies the pair around (0.05, 0.3).
+void gac_oracle_regime_counts(const double* c, int64_t n, int64_t burn_in, double c_low,
+                              double c_high, int64_t counts[3]) {
+  counts[0] = counts[1] = counts[2] = 0;
+  for (int64_t step = burn_in + 1; step <= n; ++step) {  // c[step - 1] is the cosine of update `step`
+    const double mag = std::fabs(c[step - 1]);
+    if (std::isnan(mag)) continue;
+    int regime = ORACLE_PROJECT;
+    if (mag <= c_low) regime = ORACLE_SAFE;
+    else if (mag >= c_high) regime = ORACLE_SKIP;
+    counts[regime] += 1;
+  }
+}
+
 }  // extern "C"

@@ -86,6 +86,9 @@ def lib() -> ctypes.CDLL:
         L.gac_oracle_alignment_stats.argtypes = [dp, ctypes.c_int64, ctypes.c_int64, ctypes.c_double,
                                                  ctypes.c_double, dp]
         L.gac_oracle_alignment_stats.restype = None
+        L.gac_oracle_regime_counts.argtypes = [dp, ctypes.c_int64, ctypes.c_int64, ctypes.c_double,
+                                               ctypes.c_double, i64p]
+        L.gac_oracle_regime_counts.restype = None
         _lib = L
     return _lib
 
@@ -212,3 +215,12 @@ def alignment_stats(c: np.ndarray, burn_in: int, c_low: float, q: float = 0.9):
     out = np.zeros(4, dtype=np.float64)
     lib().gac_oracle_alignment_stats(_dp(c), c.size, burn_in, c_low, q, _dp(out))
     return float(out[0]), float(out[1]), float(out[2]), int(out[3])
+
+
+def regime_counts(c: np.ndarray, burn_in: int, c_low: float, c_high: float):
+    """[safe, projected, skipped] counts of the cosines after the burn-in under one threshold pair."""
+    c = np.ascontiguousarray(c, dtype=np.float64)
+    out = np.zeros(3, dtype=np.int64)
+    lib().gac_oracle_regime_counts(_dp(c), c.size, burn_in, c_low, c_high,
+                                   out.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)))
+    return [int(x) for x in out]

@@ -104,6 +104,8 @@ def lib() -> ctypes.CDLL:
         "gac_set_thresholds": (ctypes.c_int, [vp, ctypes.c_double, ctypes.c_double]),
         "gac_history_read": (ctypes.c_int, [vp, ctypes.c_int64, dp, ctypes.POINTER(ctypes.c_int32), i64p, i64p, vp]),
         "gac_diag_summary": (ctypes.c_int, [vp, ctypes.c_int64, ctypes.POINTER(GacDiag), vp]),
+        "gac_threshold_sweep": (ctypes.c_int, [vp, ctypes.c_int64, ctypes.c_int32, dp, dp,
+                                               ctypes.POINTER(ctypes.c_int32), vp]),
         "gac_plan_query": (ctypes.c_int, [i64p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, i64p, i64p]),
         "gac_profile_enable": (ctypes.c_int, [vp, ctypes.c_int32]),
         "gac_profile_read": (ctypes.c_int, [vp, dp, dp, dp, ctypes.POINTER(ctypes.c_int32)]),
@@ -280,6 +282,15 @@ class Gac:
         d = GacDiag()
         self._check(lib().gac_diag_summary(self._ctx, burn_in, ctypes.byref(d), _stream_handle(stream)))
         return d
+
+    def gac_threshold_sweep(self, pairs, burn_in: int = 0, stream=None):
+        """[[safe, projected, skipped], ...] per (c_low, c_high) pair over the recorded steps."""
+        n = len(pairs)
+        lo = (ctypes.c_double * max(n, 1))(*[float(p[0]) for p in pairs])
+        hi = (ctypes.c_double * max(n, 1))(*[float(p[1]) for p in pairs])
+        counts = (ctypes.c_int32 * (3 * max(n, 1)))()
+        self._check(lib().gac_threshold_sweep(self._ctx, burn_in, n, lo, hi, counts, _stream_handle(stream)))
+        return [list(counts[3 * i:3 * i + 3]) for i in range(n)]
 
     def gac_profile_enable(self, on: bool) -> None:
         self._check(lib().gac_profile_enable(self._ctx, 1 if on else 0))

@@ -87,6 +87,8 @@ struct gac_ctx {
   gac_diag* dev_diag = nullptr;
   gac_diag* pinned_diag = nullptr;
   gac_diag* pinned_diag_dev = nullptr;
+  int32_t* pinned_sweep = nullptr;      // GAC_MAX_SWEEP_PAIRS x 3 counts, host-mapped
+  int32_t* pinned_sweep_dev = nullptr;
 
   std::vector<void*> state;    // device pointers of d, one per tensor
   void* state_alloc = nullptr; // owned allocation backing `state`, or null
@@ -451,6 +453,9 @@ int gac_init(gac_ctx** out, const gac_config* cfg) {
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_diag), sizeof(gac_diag)));
   GAC_HIP(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned_diag), sizeof(gac_diag), hipHostMallocMapped));
   GAC_HIP(ctx, hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->pinned_diag_dev), ctx->pinned_diag, 0));
+  GAC_HIP(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned_sweep),
+                             sizeof(int32_t) * 3 * GAC_MAX_SWEEP_PAIRS, hipHostMallocMapped));
+  GAC_HIP(ctx, hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->pinned_sweep_dev), ctx->pinned_sweep, 0));
 
   // Algorithm 1: the reference state starts at zero.
   rc = state_op(ctx, gac::kStateZero, nullptr, ctx->state.data(), nullptr);
@@ -479,6 +484,7 @@ void gac_destroy(gac_ctx* ctx) {
     if (ctx->hist_regime) (void)hipFree(ctx->hist_regime);
     if (ctx->dev_diag) (void)hipFree(ctx->dev_diag);
     if (ctx->pinned_diag) (void)hipHostFree(ctx->pinned_diag);
+    if (ctx->pinned_sweep) (void)hipHostFree(ctx->pinned_sweep);
     if (ctx->result_event) (void)hipEventDestroy(ctx->result_event);
     for (int s = 0; s < kPinnedSlots; ++s) {
       if (ctx->pinned_segs[s]) (void)hipHostFree(ctx->pinned_segs[s]);
@@ -688,6 +694,31 @@ int gac_diag_summary(gac_ctx* ctx, int64_t burn_in, gac_diag* out, void* hip_str
                                 ctx->dev_diag, ctx->pinned_diag_dev, stream));
   GAC_HIP(ctx, hipStreamSynchronize(stream));
   *out = *ctx->pinned_diag;
+  return GAC_OK;
+}
+
+int gac_threshold_sweep(gac_ctx* ctx, int64_t burn_in, int32_t n_pairs, const double* c_low,
+                        const double* c_high, int32_t* counts, void* hip_stream) {
+  if (ctx == nullptr || c_low == nullptr || c_high == nullptr || counts == nullptr || burn_in < 0 ||
+      n_pairs < 1 || n_pairs > GAC_MAX_SWEEP_PAIRS)
+    return GAC_ERR_INVALID_ARG;
+  gac::SweepPairs pairs;
+  for (int i = 0; i < GAC_MAX_SWEEP_PAIRS; ++i) {
+    const int j = i < n_pairs ? i : 0;
+    if (!(c_low[j] > 0.0) || !(c_low[j] < c_high[j])) return GAC_ERR_BAD_THRESHOLDS;
+    pairs.c_low[i] = c_low[j];
+    pairs.c_high[i] = c_high[j];
+  }
+  DeviceGuard guard(ctx->device);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  int64_t first, last;
+  int rc = recorded_range(ctx, stream, &first, &last);
+  if (rc != GAC_OK) return rc;
+  if (first < burn_in + 1) first = burn_in + 1;
+  GAC_HIP(ctx, gac::launch_sweep(ctx->hist_c, ctx->hist_regime, ctx->hist_cap, first, last, pairs,
+                                 n_pairs, ctx->pinned_sweep_dev, stream));
+  GAC_HIP(ctx, hipStreamSynchronize(stream));
+  std::memcpy(counts, ctx->pinned_sweep, sizeof(int32_t) * 3 * n_pairs);
   return GAC_OK;
 }
 

@@ -93,6 +93,14 @@ hipError_t launch_apply_adamw(int dtype, const Seg* dev_segs, const AdamSeg* dev
 
 // Sets the device-side step counter (init / reset / import); a one-thread kernel rather than
 // a memset so that it can sit in a captured graph.
+// Threshold pairs of one sweep, passed to the kernel by value.
+struct SweepPairs {
+  double c_low[64];
+  double c_high[64];
+};
+hipError_t launch_sweep(const double* hist_c, const int32_t* hist_regime, int hist_cap,
+                        int64_t first_step, int64_t last_step, const SweepPairs& pairs,
+                        int n_pairs, int32_t* host_counts, hipStream_t stream);
 hipError_t launch_set_step(int64_t* dev_step, int64_t value, hipStream_t stream);
 
 hipError_t launch_state_op(int dtype, int op, const Seg* dev_segs, int64_t n_chunks,

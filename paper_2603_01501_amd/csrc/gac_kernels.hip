@@ -881,6 +881,35 @@ __global__ __launch_bounds__(1024) void diag_kernel(const double* __restrict__ h
   if (host_out != nullptr) *host_out = d;
 }
 
+// Section 4.2 rule applied to the recorded c_t under other threshold pairs: one workgroup
+// per pair, counts combined in LDS, three integers per pair written to host-mapped memory.
+__global__ __launch_bounds__(kThreads) void sweep_kernel(const double* __restrict__ hist_c,
+                                                         const int32_t* __restrict__ hist_regime,
+                                                         int hist_cap, int64_t first_step,
+                                                         int64_t last_step, SweepPairs pairs,
+                                                         int32_t* __restrict__ host_counts) {
+  __shared__ int counts[3];
+  const int tid = threadIdx.x;
+  if (tid < 3) counts[tid] = 0;
+  __syncthreads();
+  const double c_low = pairs.c_low[blockIdx.x], c_high = pairs.c_high[blockIdx.x];
+  const int64_t n_steps = last_step >= first_step ? last_step - first_step + 1 : 0;
+  int mine[3] = {0, 0, 0};
+  for (int64_t i = tid; i < n_steps; i += kThreads) {
+    const int slot = static_cast<int>((first_step + i - 1) % hist_cap);
+    if (hist_regime[slot] < 0) continue;  // non-finite step: no cosine
+    const double mag = fabs(hist_c[slot]);
+    const int regime = mag <= c_low ? GAC_SAFE : (mag >= c_high ? GAC_SKIP : GAC_PROJECT);
+    mine[0] += regime == GAC_SAFE;
+    mine[1] += regime == GAC_PROJECT;
+    mine[2] += regime == GAC_SKIP;
+  }
+  for (int r = 0; r < 3; ++r)
+    if (mine[r]) atomicAdd(&counts[r], mine[r]);
+  __syncthreads();
+  if (tid < 3) host_counts[3 * blockIdx.x + tid] = counts[tid];
+}
+
 // ------------------------------------------------------------------ state maintenance
 
 // op kStateZero: b <- 0;  op kStateCopy: b <- a.   (init / reset / export / import)
@@ -993,6 +1022,14 @@ hipError_t launch_diag(const double* hist_c, const int32_t* hist_regime, int his
                        gac_diag* host_out, hipStream_t stream) {
   diag_kernel<<<1, 1024, 0, stream>>>(hist_c, hist_regime, hist_cap, first_step, last_step, c_low,
                                       dev_out, host_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_sweep(const double* hist_c, const int32_t* hist_regime, int hist_cap,
+                        int64_t first_step, int64_t last_step, const SweepPairs& pairs,
+                        int n_pairs, int32_t* host_counts, hipStream_t stream) {
+  sweep_kernel<<<n_pairs, kThreads, 0, stream>>>(hist_c, hist_regime, hist_cap, first_step,
+                                                 last_step, pairs, host_counts);
   return hipGetLastError();
 }
 

@@ -22,7 +22,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     L = B.lib()
     names = declared_functions()
-    assert len(names) >= 21 and "gac_init" in names and "gac_step" in names
+    assert len(names) >= 22 and "gac_threshold_sweep" in names and "gac_init" in names and "gac_step" in names
     for n in names:
         assert hasattr(L, n), f"libgac.so does not export {n}"
     assert B.lib().gac_version().decode().startswith("gac-mi355x")

@@ -102,17 +102,19 @@ def test_clipping_in_the_exchange_form_and_fused_adamw():
             assert np.max(np.abs(pg - po) - tol) <= 0.0
 
 
-def test_recorded_cosines_and_table3_statistics():
-    dtype = torch.float32
+def run_recorded_sequence(n_steps=150, capacity=64):
+    """A run with a mix of regimes and one non-finite step.  Returns the context, what the
+    library reported per step and what the oracle computes per step from the same gradients
+    (its reference is the previous finite raw gradient, as in the library)."""
     shapes = [(20000,), (33,), (4097,)]
     numel = [W.numel(x) for x in shapes]
-    ctx = B.Gac(numel, B.F32, history_capacity=64)
+    ctx = B.Gac(numel, B.F32, history_capacity=capacity)
     gen = torch.Generator(device=DEV)
     gen.manual_seed(77)
     rhos = [0.0, 0.02, 0.1, -0.2, 0.5, 0.04, -0.03, 0.25, 0.9, 0.0]
-    seen_c, seen_r = [], []
+    seen_c, seen_r, want_c, want_r = [], [], [], []
     prev = None
-    n_steps = 150
+    d_h = [np.zeros(n, dtype=np.float32) for n in numel]
     for t in range(n_steps):
         z = [torch.randn(x, generator=gen, device=DEV) for x in shapes]
         rho = rhos[t % len(rhos)]
@@ -120,27 +122,45 @@ def test_recorded_cosines_and_table3_statistics():
         if t == 100:
             g[0][3] = float("nan")
         prev = [x.clone() for x in g] if t != 100 else prev
+        g_h = U.host_copies(g)
+        dec = O.decide(O.sums(g_h, d_h, B.F32), C_LOW, C_HIGH, EPS)
+        want_c.append(dec.c)
+        want_r.append(dec.regime)
+        if not dec.nonfinite:
+            d_h = g_h
         res = B.GacResult()
         rc = B.lib().gac_step(ctx._ctx, B.ptr_list(g), None, ctypes.byref(res))
-        assert rc in (B.OK, B.ERR_NONFINITE)
+        assert rc == (B.ERR_NONFINITE if dec.nonfinite else B.OK)
         seen_c.append(res.c)
         seen_r.append(res.regime)
+    return ctx, seen_c, seen_r, np.array(want_c), want_r, prev
+
+
+def close_or_both_nan(a, b, tol=1e-6):
+    return (math.isnan(a) and math.isnan(b)) or abs(a - b) <= tol
+
+
+def test_recorded_cosines_and_table3_statistics():
+    n_steps = 150
+    ctx, seen_c, seen_r, want_c, want_r, prev = run_recorded_sequence(n_steps, 64)
+    assert all(close_or_both_nan(a, b) for a, b in zip(seen_c, want_c)) and seen_r == want_r
+    # no oracle cosine sits within rounding of a threshold, so counts can be compared exactly
+    finite = np.abs(want_c[~np.isnan(want_c)])
+    assert np.min(np.abs(finite - C_LOW)) > 1e-5 and np.min(np.abs(finite - C_HIGH)) > 1e-5
     c_hist, r_hist, first = ctx.gac_history_read()
     assert first == n_steps - 64 + 1 and len(c_hist) == 64
-    want_c = seen_c[-64:]
-    assert all((math.isnan(a) and math.isnan(b)) or a == b for a, b in zip(c_hist, want_c))
+    assert all((math.isnan(a) and math.isnan(b)) or a == b for a, b in zip(c_hist, seen_c[-64:]))
     assert r_hist == seen_r[-64:]
     assert ctx.gac_history_read(max_n=10)[2] == n_steps - 9
     for burn_in in (0, 95, 120, 149, 150, 400):
         d = ctx.gac_diag_summary(burn_in)
         lo = max(first, burn_in + 1)
-        window = np.array(seen_c[lo - 1:], dtype=np.float64)
+        window = want_c[lo - 1:]
         q, mx, frac, m = O.alignment_stats(window, 0, C_LOW)
         assert (d.n_values, d.n_nonfinite) == (m, int(np.isnan(window).sum()))
-        assert d.q90_abs_c == pytest.approx(q, rel=1e-12, abs=0) and d.max_abs_c == mx
+        assert abs(d.q90_abs_c - q) <= 1e-6 and abs(d.max_abs_c - mx) <= 1e-6
         assert d.frac_le_c_low == pytest.approx(frac, rel=1e-15, abs=0)
-        regs = [r for r, c in zip(seen_r[lo - 1:], window) if not math.isnan(c)]
-        assert list(d.regime_count) == [regs.count(B.SAFE), regs.count(B.PROJECT), regs.count(B.SKIP)]
+        assert list(d.regime_count) == O.regime_counts(window, 0, C_LOW, C_HIGH)
         if m:
             assert (d.first_step, d.last_step) == (lo, n_steps)
     # records start again after a reset
@@ -148,3 +168,40 @@ def test_recorded_cosines_and_table3_statistics():
     assert ctx.gac_history_read()[0] == [] and ctx.gac_diag_summary(0).n_values == 0
     res = ctx.gac_step(prev)
     assert ctx.gac_history_read() == ([0.0], [B.SAFE], 1)
+
+
+def test_threshold_sweep_over_the_record():
+    n_steps = 110           # step 101 is the non-finite one: no pair counts it
+    ctx, seen_c, seen_r, want_c, want_r, prev = run_recorded_sequence(n_steps, 128)
+    # a grid of the Table 4 kind around the defaults, plus a never-skip pair
+    pairs = [(lo, hi) for lo in (0.01, 0.03, 0.05, 0.1, 0.2) for hi in (0.25, 0.3, 0.4, 0.6)] + [(0.05, 2.0)]
+    finite = np.abs(want_c[~np.isnan(want_c)])
+    for lo, hi in pairs:
+        assert np.min(np.abs(finite - lo)) > 1e-5 and np.min(np.abs(finite - hi)) > 1e-5
+    for burn_in in (0, 50, 100, 101, 110):
+        got = ctx.gac_threshold_sweep(pairs, burn_in)
+        assert got == [O.regime_counts(want_c, burn_in, lo, hi) for lo, hi in pairs]
+        assert all(sum(x) == max(0, n_steps - burn_in - (burn_in <= 100)) for x in got)
+    # the pair in force reproduces the regimes the steps actually took
+    assert ctx.gac_threshold_sweep([(C_LOW, C_HIGH)])[0] == list(ctx.gac_diag_summary(0).regime_count)
+    # inclusive ends (Section 4.2): a threshold equal to a recorded |c| counts that step as
+    # safe (lower end) or as skipped (upper end)
+    c_hist = [abs(c) for c in ctx.gac_history_read()[0] if not math.isnan(c)]
+    x = sorted(c_hist)[len(c_hist) // 2]
+    safe, proj, skip = ctx.gac_threshold_sweep([(x, 10.0)])[0]
+    assert safe == sum(c <= x for c in c_hist) and skip == 0
+    safe, proj, skip = ctx.gac_threshold_sweep([(1e-12, x)])[0]
+    assert skip == sum(c >= x for c in c_hist)
+    # a ring shorter than the run only sees its last entries
+    ctx2, *_ = run_recorded_sequence(n_steps, 16)
+    assert ctx2.gac_threshold_sweep(pairs[:3], 0) == \
+        [O.regime_counts(want_c, n_steps - 16, lo, hi) for lo, hi in pairs[:3]]
+    # argument checks
+    for bad in ([(0.3, 0.3)], [(0.05, 0.3), (0.0, 0.3)], [(0.05, float("nan"))]):
+        with pytest.raises(B.GacError) as e:
+            ctx.gac_threshold_sweep(bad)
+        assert e.value.code == B.ERR_BAD_THRESHOLDS
+    for bad in ([], [(0.05, 0.3)] * 65):
+        with pytest.raises(B.GacError) as e:
+            ctx.gac_threshold_sweep(bad)
+        assert e.value.code == B.ERR_INVALID_ARG

@@ -30,6 +30,10 @@ MUTATIONS = [
     ("quantile_nearest_rank", "out[0] = a[lo] + (a[hi] - a[lo]) * (pos - static_cast<double>(lo));", "out[0] = a[hi];"),
     ("stats_ignore_burn_in", "for (int64_t t = burn_in; t < n; ++t)", "for (int64_t t = 0; t < n; ++t)"),
     ("stats_strict_threshold", "inside += (x <= c_low) ? 1 : 0;", "inside += (x < c_low) ? 1 : 0;"),
+    ("sweep_safe_exclusive", "if (mag <= c_low) regime = ORACLE_SAFE;", "if (mag < c_low) regime = ORACLE_SAFE;"),
+    ("sweep_skip_exclusive", "else if (mag >= c_high) regime = ORACLE_SKIP;", "else if (mag > c_high) regime = ORACLE_SKIP;"),
+    ("sweep_signed", "const double mag = std::fabs(c[step - 1]);", "const double mag = c[step - 1];"),
+    ("sweep_burn_in_off_by_one", "for (int64_t step = burn_in + 1; step <= n; ++step) {", "for (int64_t step = burn_in; step <= n; ++step) {"),
     ("adam_coupled_decay", "pi = pi - lr * weight_decay * pi;", "pi = pi - weight_decay * pi;"),
 ]
 

@@ -402,3 +402,29 @@ def test_alignment_stats_hand_example():
     q, mx, frac, m = O.alignment_stats(c, 1, 0.03)
     assert (m, mx) == (5, 0.10)
     assert q == pytest.approx(0.076, rel=1e-14) and frac == pytest.approx(3 / 5)
+
+
+def test_regime_counts_hand_example():
+    # Section 4.2 with (c_low, c_high) = (0.05, 0.3): |c| <= 0.05 safe, |c| >= 0.3 skip, else project.
+    # Values 0.05 and 0.3 are written as the same literals as the thresholds, so the inclusive
+    # ends are exercised exactly; the first two entries are burned in; NaN is a non-finite step.
+    c = np.array([0.9, 0.0, 0.05, -0.05, 0.051, 0.3, -0.3, 0.29, float("nan"), -0.2, 0.0, -1.0])
+    assert O.regime_counts(c, 2, 0.05, 0.3) == [3, 3, 3]
+    assert O.regime_counts(c, 0, 0.05, 0.3) == [4, 3, 4]
+    assert O.regime_counts(c, 3, 0.05, 0.3) == [2, 3, 3]
+    # other pairs of the Table 4 kind: a wider safe band / an earlier skip
+    assert O.regime_counts(c, 0, 0.2, 0.3) == [6, 1, 4]
+    assert O.regime_counts(c, 0, 0.05, 0.2) == [4, 1, 6]
+    assert O.regime_counts(c, 0, 0.05, 2.0) == [4, 7, 0]
+    assert O.regime_counts(c, len(c), 0.05, 0.3) == [0, 0, 0]
+    assert O.regime_counts(c, 1, 0.05, 0.3)[0] == 4          # c[0] = 0.9 was a skip; c[1] = 0 is safe
+
+
+def test_regime_counts_agree_with_the_step_decision():
+    # the same rule decides a step (gac_oracle_decide, pinned by the hand-worked cases): feeding
+    # sums that give a chosen c must land in the regime the sweep counts it in
+    for c in (0.0, 0.05, -0.05, 0.0500001, 0.17, -0.2999, 0.3, -0.3, 0.8):
+        s = np.array([c, 1.0, 1.0])
+        dec = O.decide(s, 0.05, 0.3, 0.0)
+        counts = O.regime_counts(np.array([c]), 0, 0.05, 0.3)
+        assert counts[dec.regime] == 1 and sum(counts) == 1
