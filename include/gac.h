@@ -143,7 +143,10 @@ void gac_destroy(gac_ctx* ctx);
 
 /* One whole update (steps 1-5 above) on one GPU.
  *   grad_ptrs  host list of n_tensors device pointers to g (modified in place only in the
- *              projection regime).  May differ from call to call; sizes may not.
+ *              projection regime).  May differ from call to call; sizes may not.  The
+ *              gradient buffers must not overlap the state buffers: a pointer equal to the
+ *              tensor's state pointer is rejected (GAC_ERR_INVALID_ARG), other overlaps are
+ *              not detected.  The same holds for every entry point that takes grad_ptrs.
  *   host_out   NULL: fully asynchronous.  Otherwise the call waits until the regime is known
  *              (pass 2 may still be running) and fills *host_out; the caller skips its
  *              optimizer step if regime is GAC_SKIP.

@@ -216,6 +216,14 @@ int check_ptrs(const gac_ctx* ctx, const void* const* ptrs) {
   return GAC_OK;
 }
 
+// In place the gradient and the reference state are read and written by the same pass, so a
+// gradient buffer that IS the state buffer cannot work; partial overlaps are the caller's to avoid.
+int check_not_state(const gac_ctx* ctx, void* const* grad_ptrs) {
+  for (int j = 0; j < ctx->n_tensors; ++j)
+    if (ctx->numel[j] > 0 && grad_ptrs[j] == ctx->state[j]) return GAC_ERR_INVALID_ARG;
+  return GAC_OK;
+}
+
 StepEvents* next_events(gac_ctx* ctx) {
   if (!ctx->profiling || ctx->prof_used >= static_cast<size_t>(kMaxProfiledSteps)) return nullptr;
   if (ctx->prof_used == ctx->prof_pool.size()) {
@@ -339,9 +347,23 @@ int gac_plan_query(const int64_t* numel, int32_t n_tensors, int32_t dtype, int32
   return GAC_OK;
 }
 
+namespace {
+int init_impl(gac_ctx** out, const gac_config* cfg);
+}
+
 int gac_init(gac_ctx** out, const gac_config* cfg) {
   if (out == nullptr) return GAC_ERR_INVALID_ARG;
   *out = nullptr;
+  try {  // host containers may throw; nothing may cross the C boundary
+    return init_impl(out, cfg);
+  } catch (...) {
+    *out = nullptr;
+    return GAC_ERR_ALLOC;
+  }
+}
+
+namespace {
+int init_impl(gac_ctx** out, const gac_config* cfg) {
   if (cfg == nullptr || cfg->n_tensors < 0 || (cfg->n_tensors > 0 && cfg->numel == nullptr) ||
       cfg->flags != 0 || cfg->grid_blocks < 0 || cfg->grid_blocks > gac::kMaxGridBlocks ||
       cfg->apply_blocks < 0 || cfg->apply_blocks > gac::kMaxGridBlocks || cfg->reserved != 0 ||
@@ -466,6 +488,7 @@ int gac_init(gac_ctx** out, const gac_config* cfg) {
   *out = ctx;
   return GAC_OK;
 }
+}  // namespace
 
 void gac_destroy(gac_ctx* ctx) {
   if (ctx == nullptr) return;
@@ -500,6 +523,7 @@ void gac_destroy(gac_ctx* ctx) {
 int gac_step(gac_ctx* ctx, void* const* grad_ptrs, void* hip_stream, gac_result* host_out) {
   if (ctx == nullptr) return GAC_ERR_INVALID_ARG;
   int rc = check_ptrs(ctx, const_cast<const void* const*>(grad_ptrs));
+  if (rc == GAC_OK) rc = check_not_state(ctx, grad_ptrs);
   if (rc != GAC_OK) return rc;
   DeviceGuard guard(ctx->device);
   return run_step(ctx, grad_ptrs, true, nullptr, ApplyKind::kPlain, nullptr,
@@ -509,9 +533,8 @@ int gac_step(gac_ctx* ctx, void* const* grad_ptrs, void* hip_stream, gac_result*
 int gac_step_exchange(gac_ctx* ctx, void** grad_ptrs, void* hip_stream, gac_result* host_out) {
   if (ctx == nullptr || host_out == nullptr || !ctx->state_is_callers) return GAC_ERR_INVALID_ARG;
   int rc = check_ptrs(ctx, const_cast<const void* const*>(grad_ptrs));
+  if (rc == GAC_OK) rc = check_not_state(ctx, grad_ptrs);
   if (rc != GAC_OK) return rc;
-  for (int j = 0; j < ctx->n_tensors; ++j)
-    if (ctx->numel[j] > 0 && grad_ptrs[j] == ctx->state[j]) return GAC_ERR_INVALID_ARG;
   DeviceGuard guard(ctx->device);
   rc = run_step(ctx, grad_ptrs, true, nullptr, ApplyKind::kExchange, nullptr,
                 static_cast<hipStream_t>(hip_stream), host_out);
@@ -543,6 +566,7 @@ int gac_apply(gac_ctx* ctx, void* const* grad_ptrs, const double* dev_sums3, voi
               gac_result* host_out) {
   if (ctx == nullptr || dev_sums3 == nullptr) return GAC_ERR_INVALID_ARG;
   int rc = check_ptrs(ctx, const_cast<const void* const*>(grad_ptrs));
+  if (rc == GAC_OK) rc = check_not_state(ctx, grad_ptrs);
   if (rc != GAC_OK) return rc;
   DeviceGuard guard(ctx->device);
   return run_step(ctx, grad_ptrs, false, dev_sums3, ApplyKind::kPlain, nullptr,
@@ -554,6 +578,7 @@ int gac_step_adamw(gac_ctx* ctx, void* const* grad_ptrs, float* const* master_p,
                    void* hip_stream, gac_result* host_out) {
   if (ctx == nullptr || hyper == nullptr) return GAC_ERR_INVALID_ARG;
   int rc = check_ptrs(ctx, const_cast<const void* const*>(grad_ptrs));
+  if (rc == GAC_OK) rc = check_not_state(ctx, grad_ptrs);
   if (rc != GAC_OK) return rc;
   if (ctx->n_tensors > 0 && (master_p == nullptr || m == nullptr || v == nullptr)) return GAC_ERR_INVALID_ARG;
   for (int j = 0; j < ctx->n_tensors; ++j) {
@@ -670,8 +695,14 @@ int gac_history_read(gac_ctx* ctx, int64_t max_n, double* c_out, int32_t* regime
   *n_out = n;
   if (first_step_out) *first_step_out = first;
   if (n == 0) return GAC_OK;
-  std::vector<double> c(ctx->hist_cap);
-  std::vector<int32_t> r(ctx->hist_cap);
+  std::vector<double> c;
+  std::vector<int32_t> r;
+  try {
+    c.resize(ctx->hist_cap);
+    r.resize(ctx->hist_cap);
+  } catch (...) {
+    return GAC_ERR_ALLOC;
+  }
   GAC_HIP(ctx, hipMemcpy(c.data(), ctx->hist_c, sizeof(double) * ctx->hist_cap, hipMemcpyDeviceToHost));
   GAC_HIP(ctx, hipMemcpy(r.data(), ctx->hist_regime, sizeof(int32_t) * ctx->hist_cap, hipMemcpyDeviceToHost));
   for (int64_t i = 0; i < n; ++i) {
@@ -724,6 +755,13 @@ int gac_threshold_sweep(gac_ctx* ctx, int64_t burn_in, int32_t n_pairs, const do
 
 int gac_profile_enable(gac_ctx* ctx, int32_t on) {
   if (ctx == nullptr) return GAC_ERR_INVALID_ARG;
+  if (on) {
+    try {
+      ctx->prof_pool.reserve(kMaxProfiledSteps);  // so that recording a step never allocates
+    } catch (...) {
+      return GAC_ERR_ALLOC;
+    }
+  }
   ctx->profiling = on != 0;
   ctx->prof_used = 0;
   return GAC_OK;

@@ -436,3 +436,14 @@ def test_async_step_replayed_from_a_hip_graph():
     assert first == 1 and len(c_hist) == 6
     assert list(zip(c_hist[1:], r_hist[1:])) == seen
     assert B.PROJECT in r_hist
+
+
+def test_gradient_buffer_that_is_the_state_buffer_is_rejected():
+    d = [torch.zeros(4096, device=DEV), torch.zeros(10, device=DEV)]
+    ctx = B.Gac([4096, 10], B.F32, state=d)
+    g = [torch.ones(4096, device=DEV), d[1]]
+    for call in (lambda: ctx.gac_step(g), lambda: ctx.gac_step_exchange(g)):
+        with pytest.raises(B.GacError) as e:
+            call()
+        assert e.value.code == B.ERR_INVALID_ARG
+    assert float(d[0].abs().sum()) == 0.0          # nothing ran
