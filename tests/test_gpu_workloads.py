@@ -101,8 +101,9 @@ def test_one_and_a_half_billion_bf16_list(rho, c_high, expect):
 
 def test_seven_billion_bf16_list_consecutive_steps():
     """7.6B-style list (255 tensors, 7,615,487,488 elements, bf16), consecutive AR(1)
-    gradients with the state carried by the library: step 1 safe (zero reference), step 2
-    projected (thresholds 0.05 / 2.0), step 3 skipped (thresholds 0.05 / 0.3)."""
+    gradients with the state carried by the library over sixteen steps: step 1 safe (zero
+    reference), step 2 projected (thresholds 0.05 / 2.0), step 3 skipped (thresholds 0.05 /
+    0.3), then alternating up to step 16."""
     dtype = torch.bfloat16
     shapes = W.MODEL_76B.tensor_shapes()
     numel = [W.numel(s) for s in shapes]
@@ -162,6 +163,40 @@ def test_seven_billion_bf16_list_consecutive_steps():
     ctx.gac_state_export(state)
     torch.cuda.synchronize()
     assert all(U.bits_equal(a, b) for a, b in zip(state, g3))
+    del g2
+
+    # steps 4-16 of the sixteen: projection forced on the even ones, the paper's thresholds on
+    # the odd ones (0.95 is far beyond c_high: skipped).  Every step is checked through
+    # properties that hold at any size; the last one also against the oracle over all elements.
+    prev_raw, prev_gg = g3, res3.gg
+    for step in range(4, 17):
+        projecting = step % 2 == 0
+        ctx.gac_set_thresholds(C_LOW, 2.0 if projecting else C_HIGH)
+        stream.next_into(g)
+        raw = U.clone_list(g)
+        r = ctx.gac_step(g)
+        torch.cuda.synchronize()
+        assert r.step == step and r.regime == (B.PROJECT if projecting else B.SKIP)
+        assert r.dd == prev_gg, "the reference is the previous raw gradient: same bits, same order"
+        assert abs(r.c - 0.95) <= 5 * (1 - 0.95 ** 2) / math.sqrt(N) + 2e-3
+        ctx.gac_state_export(state)
+        torch.cuda.synchronize()
+        assert all(U.bits_equal(a, b) for a, b in zip(state, raw)), f"state after step {step}"
+        if projecting:
+            along = sum(float(torch.dot(a.reshape(-1).double(), b.reshape(-1).double()))
+                        for a, b in zip(g, prev_raw))
+            assert along / math.sqrt(r.dd) == pytest.approx(math.copysign(C_LOW, r.c) * math.sqrt(r.gg), rel=2e-3)
+        else:
+            assert all(U.bits_equal(a, b) for a, b in zip(g, raw))
+        if step == 16:
+            say("step 16: oracle sums over all elements, projection on sampled tensors")
+            g_h, d_h, s, dec = oracle_decision(raw, prev_raw, dtype, C_LOW, 2.0)
+            check_result(r, s, dec)
+            err = check_projection(g, g_h, d_h, s, dec, dtype, sample)
+            say(f"  c={r.c:.6f} alpha={r.alpha:.6f} rel-L2(sample)={err:.2e}")
+            del g_h, d_h
+        say(f"step {step}: c={r.c:.6f} {B.REGIME_NAMES[r.regime]}")
+        prev_raw, prev_gg = raw, r.gg
     ctx.close()
 
 
