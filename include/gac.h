@@ -214,6 +214,39 @@ int gac_state_import(gac_ctx* ctx, void* const* src_ptrs, int64_t step, void* hi
 /* d <- 0 and step <- 0: back to the state right after gac_init. */
 int gac_reset(gac_ctx* ctx, void* hip_stream);
 
+/* Where the reference state sits in HBM relative to the gradients changes the speed of the
+ * in-place pass (measured on MI355X: about 10 % between two buffers in the same third of the
+ * physical memory and two buffers in different thirds; a read-only pass moves a few per cent
+ * the other way).  Physical placement cannot be requested, only observed, so this call
+ * measures: it times the reduction pass and a data-preserving probe of the in-place pass
+ * (same loads and stores, every value written back unchanged) with the state where it is and with up to
+ * max_candidates - 1 further allocations of the same size, which are held until the end so
+ * that each lands deeper in memory than the one before; it then moves the state (contents
+ * preserved bit for bit) to the location with the smallest sum of the two, frees the rest, and picks the workgroup
+ * count of the in-place pass the same way (unless gac_config.apply_blocks fixed it).
+ *   grad_ptrs        the gradient buffers the steps will use (contents preserved bit for bit;
+ *                    nothing else may touch them during the call)
+ *   max_candidates   1 .. GAC_MAX_PLACEMENT_CANDIDATES; 1 only tunes the workgroup count
+ *   max_extra_bytes  cap on the temporary device memory; 0 = whatever is free less a 4 GiB
+ *                    reserve.  The search stops quietly when memory runs out.
+ *   report           optional; what was timed and what was chosen
+ * Only for a state the library allocated (gac_config.state_ptrs == NULL), else
+ * GAC_ERR_INVALID_ARG.  Lists under 256 MiB are left alone (they are not bandwidth bound).
+ * Set-up time call: allocates, waits for the stream, cannot be captured into a graph. */
+#define GAC_MAX_PLACEMENT_CANDIDATES 16
+typedef struct gac_placement {
+  int32_t n_candidates; /* locations timed; index 0 is where the state was */
+  int32_t chosen;       /* index of the location now in use */
+  int32_t apply_blocks; /* workgroups of the in-place pass from now on */
+  int32_t n_blocks_tried;
+  double probe_ms[GAC_MAX_PLACEMENT_CANDIDATES];  /* in-place probe time per location */
+  double reduce_ms[GAC_MAX_PLACEMENT_CANDIDATES]; /* reduction pass time per location */
+  int32_t blocks_tried[4];
+  double blocks_ms[4];  /* probe time at the chosen location per workgroup count */
+} gac_placement;
+int gac_place_state(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidates,
+                    int64_t max_extra_bytes, void* hip_stream, gac_placement* report);
+
 /* Replaces the thresholds (validated as in gac_init) for the following steps. */
 int gac_set_thresholds(gac_ctx* ctx, double c_low, double c_high);
 

@@ -55,6 +55,17 @@ class GacDiag(ctypes.Structure):
                 ("max_abs_c", ctypes.c_double), ("frac_le_c_low", ctypes.c_double)]
 
 
+MAX_PLACEMENT_CANDIDATES = 16
+
+
+class GacPlacement(ctypes.Structure):
+    _fields_ = [("n_candidates", ctypes.c_int32), ("chosen", ctypes.c_int32),
+                ("apply_blocks", ctypes.c_int32), ("n_blocks_tried", ctypes.c_int32),
+                ("probe_ms", ctypes.c_double * MAX_PLACEMENT_CANDIDATES),
+                ("reduce_ms", ctypes.c_double * MAX_PLACEMENT_CANDIDATES),
+                ("blocks_tried", ctypes.c_int32 * 4), ("blocks_ms", ctypes.c_double * 4)]
+
+
 class GacAdamWHyper(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
                 ("eps_adam", ctypes.c_double), ("weight_decay", ctypes.c_double),
@@ -106,6 +117,8 @@ def lib() -> ctypes.CDLL:
         "gac_diag_summary": (ctypes.c_int, [vp, ctypes.c_int64, ctypes.POINTER(GacDiag), vp]),
         "gac_threshold_sweep": (ctypes.c_int, [vp, ctypes.c_int64, ctypes.c_int32, dp, dp,
                                                ctypes.POINTER(ctypes.c_int32), vp]),
+        "gac_place_state": (ctypes.c_int, [vp, vpp, ctypes.c_int32, ctypes.c_int64, vp,
+                                           ctypes.POINTER(GacPlacement)]),
         "gac_plan_query": (ctypes.c_int, [i64p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, i64p, i64p]),
         "gac_profile_enable": (ctypes.c_int, [vp, ctypes.c_int32]),
         "gac_profile_read": (ctypes.c_int, [vp, dp, dp, dp, ctypes.POINTER(ctypes.c_int32)]),
@@ -282,6 +295,13 @@ class Gac:
         d = GacDiag()
         self._check(lib().gac_diag_summary(self._ctx, burn_in, ctypes.byref(d), _stream_handle(stream)))
         return d
+
+    def gac_place_state(self, grads, max_candidates: int = MAX_PLACEMENT_CANDIDATES,
+                        max_extra_bytes: int = 0, stream=None) -> GacPlacement:
+        rep = GacPlacement()
+        self._check(lib().gac_place_state(self._ctx, ptr_list(grads), max_candidates, max_extra_bytes,
+                                          _stream_handle(stream), ctypes.byref(rep)))
+        return rep
 
     def gac_threshold_sweep(self, pairs, burn_in: int = 0, stream=None):
         """[[safe, projected, skipped], ...] per (c_low, c_high) pair over the recorded steps."""

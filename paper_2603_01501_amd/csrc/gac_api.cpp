@@ -75,6 +75,8 @@ struct gac_ctx {
   int grid_state = 1;  // workgroups of the state maintenance kernel
   int grid_apply = 1;  // workgroups of the apply kernel
   int grid_adamw = 1;  // workgroups of the fused AdamW apply kernel
+  bool apply_blocks_fixed = false;  // gac_config.apply_blocks was given: never re-tuned
+  int cus = 1;
   double c_low = 0, c_high = 0, eps = 0, beta = 1;
   double max_grad_norm = 0;
   int64_t* dev_step = nullptr;  // the step counter lives on the device (see DecideParams)
@@ -221,6 +223,32 @@ int check_ptrs(const gac_ctx* ctx, const void* const* ptrs) {
 int check_not_state(const gac_ctx* ctx, void* const* grad_ptrs) {
   for (int j = 0; j < ctx->n_tensors; ++j)
     if (ctx->numel[j] > 0 && grad_ptrs[j] == ctx->state[j]) return GAC_ERR_INVALID_ARG;
+  return GAC_OK;
+}
+
+// One allocation for the whole state, every tensor's slice 256-byte aligned.
+int64_t state_block_bytes(const gac_ctx* ctx) {
+  const int64_t es = elem_size(ctx->dtype);
+  int64_t bytes = 0;
+  for (int j = 0; j < ctx->n_tensors; ++j) bytes += (ctx->numel[j] * es + 255) / 256 * 256;
+  return bytes;
+}
+
+int alloc_state_block(gac_ctx* ctx, void** alloc, std::vector<void*>* ptrs) {
+  const int64_t es = elem_size(ctx->dtype);
+  const int64_t bytes = state_block_bytes(ctx);
+  *alloc = nullptr;
+  if (bytes > 0 && hipMalloc(alloc, static_cast<size_t>(bytes)) != hipSuccess) {
+    (void)hipGetLastError();
+    *alloc = nullptr;
+    return GAC_ERR_ALLOC;
+  }
+  ptrs->assign(ctx->n_tensors, nullptr);
+  int64_t off = 0;
+  for (int j = 0; j < ctx->n_tensors; ++j) {
+    (*ptrs)[j] = static_cast<char*>(*alloc) + off;
+    off += (ctx->numel[j] * es + 255) / 256 * 256;
+  }
   return GAC_OK;
 }
 
@@ -420,6 +448,8 @@ int init_impl(gac_ctx** out, const gac_config* cfg) {
   // reduction does best with one workgroup per CU, the in-place pass with workgroups on
   // three quarters of the CUs; more requesters lower the achieved HBM bandwidth.
   const int64_t cus = prop.multiProcessorCount;
+  ctx->cus = static_cast<int>(cus);
+  ctx->apply_blocks_fixed = cfg->apply_blocks > 0;
   ctx->grid = pick_grid(cfg->grid_blocks, cus);
   ctx->grid_state = pick_grid(0, cus * 4);
   ctx->grid_apply = pick_grid(cfg->apply_blocks, cus * 3 / 4);
@@ -430,21 +460,8 @@ int init_impl(gac_ctx** out, const gac_config* cfg) {
     for (int j = 0; j < n; ++j) ctx->state[j] = cfg->state_ptrs[j];
     ctx->state_is_callers = true;
   } else {
-    // one allocation, every tensor's slice 256-byte aligned
-    const int64_t es = elem_size(ctx->dtype);
-    int64_t bytes = 0;
-    std::vector<int64_t> off(n);
-    for (int j = 0; j < n; ++j) {
-      off[j] = bytes;
-      bytes += (ctx->numel[j] * es + 255) / 256 * 256;
-    }
-    if (bytes > 0) {
-      if (hipMalloc(&ctx->state_alloc, static_cast<size_t>(bytes)) != hipSuccess) {
-        (void)hipGetLastError();
-        return GAC_ERR_ALLOC;
-      }
-    }
-    for (int j = 0; j < n; ++j) ctx->state[j] = static_cast<char*>(ctx->state_alloc) + off[j];
+    rc = alloc_state_block(ctx, &ctx->state_alloc, &ctx->state);
+    if (rc != GAC_OK) return rc;
   }
   rc = check_ptrs(ctx, const_cast<const void* const*>(ctx->state.data()));
   if (rc != GAC_OK) return rc;
@@ -654,6 +671,167 @@ int gac_reset(gac_ctx* ctx, void* hip_stream) {
     GAC_HIP(ctx, gac::launch_set_step(ctx->dev_step, 0, static_cast<hipStream_t>(hip_stream)));
     ctx->hist_first = 1;
   }
+  return rc;
+}
+
+namespace {
+// Median time of three launches (after one untimed) of the in-place probe, or of the
+// reduction pass when `reduce` is set, with the state at `state_ptrs`.
+int time_probe(gac_ctx* ctx, void* const* grad_ptrs, void* const* state_ptrs, bool reduce, int grid,
+               hipStream_t stream, hipEvent_t e0, hipEvent_t e1, double* ms_out) {
+  int rc = upload_segs(ctx, const_cast<const void* const*>(grad_ptrs), state_ptrs, stream);
+  if (rc != GAC_OK) return rc;
+  float ms[3];
+  for (int i = -1; i < 3; ++i) {
+    GAC_HIP(ctx, hipEventRecord(e0, stream));
+    if (reduce) {
+      GAC_HIP(ctx, gac::launch_reduce(ctx->dtype, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
+                                      ctx->dev_partials, ctx->grid, stream));
+    } else {
+      GAC_HIP(ctx, gac::launch_apply_probe(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
+                                           ctx->chunk_elems, grid, stream));
+    }
+    GAC_HIP(ctx, hipEventRecord(e1, stream));
+    GAC_HIP(ctx, hipEventSynchronize(e1));
+    if (i >= 0) GAC_HIP(ctx, hipEventElapsedTime(&ms[i], e0, e1));
+  }
+  const float lo = ms[0] < ms[1] ? ms[0] : ms[1], hi = ms[0] < ms[1] ? ms[1] : ms[0];
+  *ms_out = ms[2] < lo ? lo : (ms[2] > hi ? hi : ms[2]);
+  return GAC_OK;
+}
+
+// Both passes of a step with the state at one candidate location.
+int time_candidate(gac_ctx* ctx, void* const* grad_ptrs, void* const* state_ptrs, hipStream_t stream,
+                   hipEvent_t e0, hipEvent_t e1, double* probe_ms, double* reduce_ms) {
+  int rc = time_probe(ctx, grad_ptrs, state_ptrs, false, ctx->grid_apply, stream, e0, e1, probe_ms);
+  if (rc == GAC_OK) rc = time_probe(ctx, grad_ptrs, state_ptrs, true, 0, stream, e0, e1, reduce_ms);
+  return rc;
+}
+
+struct Candidate {
+  void* alloc = nullptr;
+  std::vector<void*> ptrs;
+};
+
+int place_state_impl(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidates,
+                     int64_t max_extra_bytes, hipStream_t stream, gac_placement* rep) {
+  constexpr int64_t kMinBytes = 256ll << 20, kReserve = 4ll << 30;
+  rep->n_candidates = 1;
+  rep->chosen = 0;
+  rep->apply_blocks = ctx->grid_apply;
+  const int64_t bytes = state_block_bytes(ctx);
+  if (bytes < kMinBytes) return GAC_OK;
+  GAC_HIP(ctx, hipStreamSynchronize(stream));
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  GAC_HIP(ctx, hipEventCreate(&e0));
+  if (hipEventCreate(&e1) != hipSuccess) {
+    (void)hipEventDestroy(e0);
+    return fail_hip(ctx, hipGetLastError(), "hipEventCreate");
+  }
+  std::vector<Candidate> cand(1);
+  cand[0].alloc = ctx->state_alloc;
+  cand[0].ptrs = ctx->state;
+  auto cleanup = [&](int keep) {  // frees every candidate this call allocated except `keep`
+    for (int c = 1; c < static_cast<int>(cand.size()); ++c)
+      if (c != keep && cand[c].alloc) (void)hipFree(cand[c].alloc);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+  };
+  int rc = time_candidate(ctx, grad_ptrs, cand[0].ptrs.data(), stream, e0, e1, &rep->probe_ms[0],
+                          &rep->reduce_ms[0]);
+  int64_t extra = 0;
+  while (rc == GAC_OK && static_cast<int>(cand.size()) < max_candidates) {
+    size_t free_b = 0, total_b = 0;
+    if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) {
+      (void)hipGetLastError();
+      break;
+    }
+    if (static_cast<int64_t>(free_b) < bytes + kReserve) break;
+    if (max_extra_bytes > 0 && extra + bytes > max_extra_bytes) break;
+    Candidate c;
+    if (alloc_state_block(ctx, &c.alloc, &c.ptrs) != GAC_OK) break;  // out of memory: stop quietly
+    extra += bytes;
+    cand.push_back(c);
+    const int i = static_cast<int>(cand.size()) - 1;
+    rc = time_candidate(ctx, grad_ptrs, cand[i].ptrs.data(), stream, e0, e1, &rep->probe_ms[i],
+                        &rep->reduce_ms[i]);
+  }
+  if (rc != GAC_OK) {
+    cleanup(-1);
+    ctx->segs_valid = false;
+    return rc;
+  }
+  rep->n_candidates = static_cast<int>(cand.size());
+  auto both = [&](int c) { return rep->probe_ms[c] + rep->reduce_ms[c]; };
+  int best = 0;
+  for (int c = 1; c < rep->n_candidates; ++c)
+    if (both(c) < both(best)) best = c;
+  if (both(best) > 0.99 * both(0)) best = 0;  // not worth a move
+  if (best != 0) {
+    rc = state_op(ctx, gac::kStateCopy, const_cast<const void* const*>(ctx->state.data()),
+                  cand[best].ptrs.data(), stream);
+    if (rc == GAC_OK && hipStreamSynchronize(stream) != hipSuccess) rc = fail_hip(ctx, hipGetLastError(), "hipStreamSynchronize");
+    if (rc != GAC_OK) {
+      cleanup(-1);
+      ctx->segs_valid = false;
+      return rc;
+    }
+    (void)hipFree(ctx->state_alloc);
+    ctx->state_alloc = cand[best].alloc;
+    ctx->state = cand[best].ptrs;
+  }
+  rep->chosen = best;
+  // workgroup count of the in-place pass at the chosen location
+  if (!ctx->apply_blocks_fixed) {
+    const int64_t tries[3] = {ctx->cus * 3ll / 4, ctx->cus, 2ll * ctx->cus};
+    int n = 0, best_blocks = ctx->grid_apply;
+    double best_ms = 0.0;
+    for (int64_t b : tries) {
+      if (b < 1) b = 1;
+      if (b > ctx->n_chunks) b = ctx->n_chunks;
+      if (b > gac::kMaxGridBlocks) b = gac::kMaxGridBlocks;
+      bool seen = false;
+      for (int i = 0; i < n; ++i) seen = seen || rep->blocks_tried[i] == b;
+      if (seen) continue;
+      double ms = 0.0;
+      rc = time_probe(ctx, grad_ptrs, ctx->state.data(), false, static_cast<int>(b), stream, e0, e1, &ms);
+      if (rc != GAC_OK) break;
+      rep->blocks_tried[n] = static_cast<int32_t>(b);
+      rep->blocks_ms[n] = ms;
+      if (n == 0 || ms < best_ms) {
+        best_ms = ms;
+        best_blocks = static_cast<int>(b);
+      }
+      ++n;
+    }
+    rep->n_blocks_tried = n;
+    if (rc == GAC_OK) ctx->grid_apply = best_blocks;
+  }
+  rep->apply_blocks = ctx->grid_apply;
+  cleanup(best);
+  ctx->segs_valid = false;
+  return rc;
+}
+}  // namespace
+
+int gac_place_state(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidates,
+                    int64_t max_extra_bytes, void* hip_stream, gac_placement* report) {
+  if (ctx == nullptr || ctx->state_is_callers || max_candidates < 1 ||
+      max_candidates > GAC_MAX_PLACEMENT_CANDIDATES || max_extra_bytes < 0)
+    return GAC_ERR_INVALID_ARG;
+  int rc = check_ptrs(ctx, const_cast<const void* const*>(grad_ptrs));
+  if (rc == GAC_OK) rc = check_not_state(ctx, grad_ptrs);
+  if (rc != GAC_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  gac_placement local;
+  std::memset(&local, 0, sizeof(local));
+  try {
+    rc = place_state_impl(ctx, grad_ptrs, max_candidates, max_extra_bytes,
+                          static_cast<hipStream_t>(hip_stream), &local);
+  } catch (...) {
+    rc = GAC_ERR_ALLOC;
+  }
+  if (report != nullptr) *report = local;
   return rc;
 }
 

@@ -86,6 +86,9 @@ hipError_t launch_exchange(int dtype, const Seg* dev_segs, int n_tensors, int64_
                            int chunk_elems, const gac_result* dev_result, int grid,
                            hipStream_t stream);
 
+// The same traffic as the projecting apply pass with every value written back unchanged.
+hipError_t launch_apply_probe(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
+                              int chunk_elems, int grid, hipStream_t stream);
 hipError_t launch_apply_adamw(int dtype, const Seg* dev_segs, const AdamSeg* dev_adam,
                               int n_tensors, int64_t n_chunks, int chunk_elems,
                               const gac_result* dev_result, AdamScalars h, int grid,

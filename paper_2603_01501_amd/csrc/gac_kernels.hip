@@ -50,9 +50,12 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // flight; more resident waves only add contention at the memory controllers.
 // Pass 1 is a pure read stream: one 256-thread workgroup per CU, 8 x 16 B loads per array
 // in flight per lane, non-temporal loads (7.2 TB/s; 6.7 with six workgroups per CU).
-// Pass 2 reads and writes the same lines: 1024-thread workgroups that load a whole 64 KiB
-// chunk of each array and then store it (4 vectors per lane), on 3/4 of the CUs,
-// non-temporal loads and stores (5.4 TB/s; 5.3 on all CUs; 5.0 with 256-thread workgroups).
+// Pass 2 reads and writes the same lines: 512-thread workgroups that load a whole 64 KiB
+// chunk of each array and then store it (8 vectors per lane), on 3/4 of the CUs or on all of
+// them (gac_place_state measures which), non-temporal loads and stores.  Where the two
+// arrays sit in HBM matters more than any of this: 5.4 TB/s with g and d in the same third of
+// the physical memory, 6.2-6.3 TB/s in different thirds (1024 x 4 tiles: 1.5 % slower there,
+// 1 % faster in the same third; 256-thread workgroups: 5.0).
 #ifndef GAC_REDUCE_THREADS
 #define GAC_REDUCE_THREADS 256
 #endif
@@ -66,10 +69,10 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #define GAC_REDUCE_DOT2 0
 #endif
 #ifndef GAC_APPLY_THREADS
-#define GAC_APPLY_THREADS 1024
+#define GAC_APPLY_THREADS 512
 #endif
 #ifndef GAC_APPLY_UNROLL
-#define GAC_APPLY_UNROLL 4
+#define GAC_APPLY_UNROLL 8
 #endif
 #ifndef GAC_APPLY_NT_LOAD
 #define GAC_APPLY_NT_LOAD 1
@@ -443,7 +446,7 @@ __device__ __forceinline__ u32x4 project_vec(u32x4 a, u32x4 b, float k, float be
 }
 
 // A chunk that is not a whole tile (the tail of a tensor, or a non-default chunk size).
-template <int DT, int T, int U>
+template <int DT, int T, int U, bool PROBE>
 __device__ __forceinline__ void apply_chunk_generic(const Chunk& ch, bool project, float k,
                                                     float beta) {
   constexpr int N = Elem<DT>::kPerVec;
@@ -455,11 +458,11 @@ __device__ __forceinline__ void apply_chunk_generic(const Chunk& ch, bool projec
   if (project) {
     for (int i = tid; i < nvec; i += T) {
       const u32x4 a = ld16<GAC_APPLY_NT_LOAD>(gv + i), b = ld16<GAC_APPLY_NT_LOAD>(dv + i);
-      st16<GAC_APPLY_NT_STORE>(gv + i, project_vec<DT>(a, b, k, beta));
-      st16<GAC_APPLY_NT_STORE>(dv + i, a);
+      st16<GAC_APPLY_NT_STORE>(gv + i, PROBE ? a : project_vec<DT>(a, b, k, beta));
+      st16<GAC_APPLY_NT_STORE>(dv + i, PROBE ? b : a);
     }
     const int e = nvec * N + tid;  // at most N-1 leftover elements
-    if (e < ch.len) {
+    if (!PROBE && e < ch.len) {
       const float x = load_elem<DT>(ch.a, e), y = load_elem<DT>(ch.b, e);
       copy_elem<DT>(ch.a, ch.b, e);
       store_elem<DT>(ga, e, fmaf(k, y, beta * x));
@@ -482,17 +485,21 @@ __device__ __forceinline__ void apply_chunk_generic(const Chunk& ch, bool projec
 // streamed the list front to back, so its last chunks would be the ones still cached).  With
 // the non-temporal loads of pass 1 this measured no different from a forward walk on 2-3 GB
 // lists; it is kept because it costs nothing.
-template <int DT, int T, int U>
+//
+// PROBE = true is the placement probe: the same loads and stores of both arrays, but every
+// value is written back where it came from (g <- g, d <- d), so nothing changes; it is timed
+// to compare candidate locations of the state (gac_place_state).
+template <int DT, int T, int U, bool PROBE>
 __global__ __launch_bounds__(T) void apply_kernel(const Seg* __restrict__ segs,
                                                          int n_tensors, int64_t n_chunks,
                                                          int chunk_elems,
                                                          const gac_result* __restrict__ res) {
   constexpr int N = Elem<DT>::kPerVec;
-  if (res->nonfinite) return;  // convention: a non-finite step modifies nothing
+  if (!PROBE && res->nonfinite) return;  // convention: a non-finite step modifies nothing
   // g <- scale_g * g + coef_d * d when the step projects and/or clips, else g stays
-  const bool project = res->modified != 0;
-  const float k = static_cast<float>(res->coef_d);
-  const float beta = static_cast<float>(res->scale_g);
+  const bool project = PROBE || res->modified != 0;
+  const float k = PROBE ? 0.0f : static_cast<float>(res->coef_d);
+  const float beta = PROBE ? 1.0f : static_cast<float>(res->scale_g);
   const int tid = threadIdx.x;
 
   struct Tile {
@@ -517,8 +524,8 @@ __global__ __launch_bounds__(T) void apply_kernel(const Seg* __restrict__ segs,
     if (project) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        st16<GAC_APPLY_NT_STORE>(gv + u * T, project_vec<DT>(tl.a[u], tl.b[u], k, beta));
-        st16<GAC_APPLY_NT_STORE>(dv + u * T, tl.a[u]);
+        st16<GAC_APPLY_NT_STORE>(gv + u * T, PROBE ? tl.a[u] : project_vec<DT>(tl.a[u], tl.b[u], k, beta));
+        st16<GAC_APPLY_NT_STORE>(dv + u * T, PROBE ? tl.b[u] : tl.a[u]);
       }
     } else {
 #pragma unroll
@@ -547,7 +554,7 @@ __global__ __launch_bounds__(T) void apply_kernel(const Seg* __restrict__ segs,
     if (cur_whole) {
       store_tile(cur, tc);
     } else {
-      apply_chunk_generic<DT, T, U>(cur, project, k, beta);
+      apply_chunk_generic<DT, T, U, PROBE>(cur, project, k, beta);
     }
     if (!more) break;
     cur = next;
@@ -981,11 +988,23 @@ hipError_t launch_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n
                         int chunk_elems, const gac_result* dev_result, int grid,
                         hipStream_t stream) {
   if (dtype == GAC_F32) {
-    apply_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
+    apply_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL, false><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
         dev_segs, n_tensors, n_chunks, chunk_elems, dev_result);
   } else {
-    apply_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
+    apply_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL, false><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
         dev_segs, n_tensors, n_chunks, chunk_elems, dev_result);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_apply_probe(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
+                              int chunk_elems, int grid, hipStream_t stream) {
+  if (dtype == GAC_F32) {
+    apply_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL, true><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
+        dev_segs, n_tensors, n_chunks, chunk_elems, nullptr);
+  } else {
+    apply_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL, true><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
+        dev_segs, n_tensors, n_chunks, chunk_elems, nullptr);
   }
   return hipGetLastError();
 }

@@ -22,7 +22,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     L = B.lib()
     names = declared_functions()
-    assert len(names) >= 22 and "gac_threshold_sweep" in names and "gac_init" in names and "gac_step" in names
+    assert len(names) >= 23 and "gac_threshold_sweep" in names and "gac_place_state" in names and "gac_init" in names and "gac_step" in names
     for n in names:
         assert hasattr(L, n), f"libgac.so does not export {n}"
     assert B.lib().gac_version().decode().startswith("gac-mi355x")
@@ -33,6 +33,7 @@ def test_struct_layouts_match_header():
     assert ctypes.sizeof(B.GacDiag) == 80
     assert ctypes.sizeof(B.GacAdamWHyper) == 48
     assert ctypes.sizeof(B.GacConfig) == 96
+    assert ctypes.sizeof(B.GacPlacement) == 320
 
 
 def test_default_config_is_the_papers():

@@ -447,3 +447,51 @@ def test_gradient_buffer_that_is_the_state_buffer_is_rejected():
             call()
         assert e.value.code == B.ERR_INVALID_ARG
     assert float(d[0].abs().sum()) == 0.0          # nothing ran
+
+
+def test_state_placement_preserves_contents_and_results():
+    """gac_place_state may move the state and re-tune the launch, but gradients and state keep
+    their bits and the following steps give what they gave before."""
+    dtype = torch.bfloat16
+    shapes = [(4096, 8192), (1,), (8192, 4096), (333, 777), (0,), (4096, 8200)]   # ~200 MiB + tails
+    numel = [W.numel(x) for x in shapes]
+    g, d0 = W.correlated_pair(shapes, dtype, 0.15, 1e-3, config_id=41, device=DEV)
+    ctx = B.Gac(numel, B.BF16)
+    ctx.gac_state_import(d0, 0)
+    g_before = U.clone_list(g)
+    # below the size limit nothing is attempted
+    rep = ctx.gac_place_state(g, 4)
+    assert (rep.n_candidates, rep.chosen) == (1, 0)
+    ctx.close()
+
+    big = [(8192, 8192), (8192, 8192), (5, 7), (8192, 8200)]       # ~400 MiB: above the limit
+    numel = [W.numel(x) for x in big]
+    g, d0 = W.correlated_pair(big, dtype, 0.15, 1e-3, config_id=42, device=DEV)
+    ctx = B.Gac(numel, B.BF16)
+    ctx.gac_state_import(d0, 0)
+    g_before = U.clone_list(g)
+    rep = ctx.gac_place_state(g, 4, max_extra_bytes=2 << 30)
+    torch.cuda.synchronize()
+    assert 1 <= rep.n_candidates <= 4 and 0 <= rep.chosen < rep.n_candidates
+    assert all(rep.probe_ms[i] > 0 for i in range(rep.n_candidates))
+    assert rep.apply_blocks in list(rep.blocks_tried[:rep.n_blocks_tried])
+    assert all(U.bits_equal(a, b) for a, b in zip(g, g_before)), "the probe must not change the gradients"
+    out = [torch.empty_like(t) for t in d0]
+    ctx.gac_state_export(out)
+    torch.cuda.synchronize()
+    assert all(U.bits_equal(a, b) for a, b in zip(out, d0)), "the state must survive the move"
+    # a step after the move against the oracle
+    g_h, d_h = U.host_copies(g), U.host_copies(d0)
+    res = ctx.gac_step(g)
+    torch.cuda.synchronize()
+    want, s, dec = O.step(g_h, d_h, B.BF16, 0.05, 0.3, 1e-8)
+    assert res.regime == dec.regime == B.PROJECT and abs(res.c - dec.c) <= U.COS_TOL
+    assert U.rel_l2(g, want) <= U.GRAD_TOL[B.BF16]
+    ctx.gac_state_export(out)
+    torch.cuda.synchronize()
+    assert all(U.bits_equal(a, b) for a, b in zip(out, g_before))
+    # a caller-provided state cannot be moved
+    ctx2 = B.Gac(numel, B.BF16, state=[torch.zeros_like(t) for t in g])
+    with pytest.raises(B.GacError) as e:
+        ctx2.gac_place_state(g, 2)
+    assert e.value.code == B.ERR_INVALID_ARG
