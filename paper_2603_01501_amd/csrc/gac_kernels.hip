@@ -445,6 +445,16 @@ __device__ __forceinline__ u32x4 project_vec(u32x4 a, u32x4 b, float k, float be
   return pack<DT>(x);
 }
 
+// Placement probe: the projected vector is computed like in a real step (with k = 0 and
+// beta = 1 it equals g unless d holds a non-finite value) and g's own bits are stored
+// whenever the two differ, so the probe does the arithmetic of the pass and changes nothing.
+__device__ __forceinline__ u32x4 same_or(u32x4 computed, u32x4 original) {
+  u32x4 out;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) out[i] = computed[i] == original[i] ? computed[i] : original[i];
+  return out;
+}
+
 // A chunk that is not a whole tile (the tail of a tensor, or a non-default chunk size).
 template <int DT, int T, int U, bool PROBE>
 __device__ __forceinline__ void apply_chunk_generic(const Chunk& ch, bool project, float k,
@@ -458,7 +468,8 @@ __device__ __forceinline__ void apply_chunk_generic(const Chunk& ch, bool projec
   if (project) {
     for (int i = tid; i < nvec; i += T) {
       const u32x4 a = ld16<GAC_APPLY_NT_LOAD>(gv + i), b = ld16<GAC_APPLY_NT_LOAD>(dv + i);
-      st16<GAC_APPLY_NT_STORE>(gv + i, PROBE ? a : project_vec<DT>(a, b, k, beta));
+      const u32x4 r = project_vec<DT>(a, b, k, beta);
+      st16<GAC_APPLY_NT_STORE>(gv + i, PROBE ? same_or(r, a) : r);
       st16<GAC_APPLY_NT_STORE>(dv + i, PROBE ? b : a);
     }
     const int e = nvec * N + tid;  // at most N-1 leftover elements
@@ -486,20 +497,21 @@ __device__ __forceinline__ void apply_chunk_generic(const Chunk& ch, bool projec
 // the non-temporal loads of pass 1 this measured no different from a forward walk on 2-3 GB
 // lists; it is kept because it costs nothing.
 //
-// PROBE = true is the placement probe: the same loads and stores of both arrays, but every
-// value is written back where it came from (g <- g, d <- d), so nothing changes; it is timed
-// to compare candidate locations of the state (gac_place_state).
+// PROBE = true is the placement probe: the same loads, arithmetic and stores, but every value
+// is written back where it came from (g <- g, d <- d), so nothing changes; it is timed to
+// compare candidate locations of the state (gac_place_state).
 template <int DT, int T, int U, bool PROBE>
 __global__ __launch_bounds__(T) void apply_kernel(const Seg* __restrict__ segs,
                                                          int n_tensors, int64_t n_chunks,
                                                          int chunk_elems,
-                                                         const gac_result* __restrict__ res) {
+                                                         const gac_result* __restrict__ res,
+                                                         float probe_k, float probe_beta) {
   constexpr int N = Elem<DT>::kPerVec;
   if (!PROBE && res->nonfinite) return;  // convention: a non-finite step modifies nothing
   // g <- scale_g * g + coef_d * d when the step projects and/or clips, else g stays
   const bool project = PROBE || res->modified != 0;
-  const float k = PROBE ? 0.0f : static_cast<float>(res->coef_d);
-  const float beta = PROBE ? 1.0f : static_cast<float>(res->scale_g);
+  const float k = PROBE ? probe_k : static_cast<float>(res->coef_d);
+  const float beta = PROBE ? probe_beta : static_cast<float>(res->scale_g);
   const int tid = threadIdx.x;
 
   struct Tile {
@@ -524,7 +536,8 @@ __global__ __launch_bounds__(T) void apply_kernel(const Seg* __restrict__ segs,
     if (project) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        st16<GAC_APPLY_NT_STORE>(gv + u * T, PROBE ? tl.a[u] : project_vec<DT>(tl.a[u], tl.b[u], k, beta));
+        const u32x4 r = project_vec<DT>(tl.a[u], tl.b[u], k, beta);
+        st16<GAC_APPLY_NT_STORE>(gv + u * T, PROBE ? same_or(r, tl.a[u]) : r);
         st16<GAC_APPLY_NT_STORE>(dv + u * T, PROBE ? tl.b[u] : tl.a[u]);
       }
     } else {
@@ -989,10 +1002,10 @@ hipError_t launch_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n
                         hipStream_t stream) {
   if (dtype == GAC_F32) {
     apply_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL, false><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result);
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, 0.0f, 1.0f);
   } else {
     apply_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL, false><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result);
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, 0.0f, 1.0f);
   }
   return hipGetLastError();
 }
@@ -1001,10 +1014,10 @@ hipError_t launch_apply_probe(int dtype, const Seg* dev_segs, int n_tensors, int
                               int chunk_elems, int grid, hipStream_t stream) {
   if (dtype == GAC_F32) {
     apply_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL, true><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, nullptr);
+        dev_segs, n_tensors, n_chunks, chunk_elems, nullptr, 0.0f, 1.0f);
   } else {
     apply_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL, true><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, nullptr);
+        dev_segs, n_tensors, n_chunks, chunk_elems, nullptr, 0.0f, 1.0f);
   }
   return hipGetLastError();
 }
