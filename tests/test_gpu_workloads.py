@@ -120,6 +120,11 @@ def test_seven_billion_bf16_list_consecutive_steps():
     assert (res.c, res.regime, res.dd, res.step) == (0.0, B.SAFE, 0.0, 1)
     assert all(U.bits_equal(a, b) for a, b in zip(g, g1))
 
+    # the launch configuration the benchmark times: state moved to the measured-best location
+    rep = ctx.gac_place_state(g)
+    say(f"placement: {rep.n_candidates} locations timed, chose {rep.chosen}, apply on {rep.apply_blocks} workgroups")
+    assert all(U.bits_equal(a, b) for a, b in zip(g, g1)), "the placement probe must not change g"
+
     say("step 2: GPU")
     stream.next_into(g)
     g2 = U.clone_list(g)
