@@ -262,7 +262,7 @@ def main():
                 "reduce_ms": [round(rep.reduce_ms[i], 3) for i in range(rep.n_candidates)],
                 "apply_blocks": rep.apply_blocks,
                 "ms_per_step_before_placement": sum(ms_before) / len(ms_before)}
-            settle(ctx, (rep.n_candidates - 1) * float(N) * es)
+            settle(ctx, (rep.n_candidates - 1) * max(float(N) * es, 12.0 * 2 ** 30))
         ctx.gac_profile_enable(True)
         ms, res = timed_steps(ctx, stream, g, steps, torch)
         k_red, k_fin, k_app, n = ctx.gac_profile_read()

@@ -716,6 +716,10 @@ struct Candidate {
 int place_state_impl(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidates,
                      int64_t max_extra_bytes, hipStream_t stream, gac_placement* rep) {
   constexpr int64_t kMinBytes = 256ll << 20, kReserve = 4ll << 30;
+  // Successive candidates start at least this much deeper in memory than the one before
+  // (the regions that matter are ~90 GiB wide); a state smaller than the stride gets spacers,
+  // allocated in pieces small enough for the driver to pack them one after the other.
+  constexpr int64_t kStride = 12ll << 30, kSpacerPiece = 1ll << 30;
   rep->n_candidates = 1;
   rep->chosen = 0;
   rep->apply_blocks = ctx->grid_apply;
@@ -731,9 +735,11 @@ int place_state_impl(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidate
   std::vector<Candidate> cand(1);
   cand[0].alloc = ctx->state_alloc;
   cand[0].ptrs = ctx->state;
+  std::vector<void*> spacers;
   auto cleanup = [&](int keep) {  // frees every candidate this call allocated except `keep`
     for (int c = 1; c < static_cast<int>(cand.size()); ++c)
       if (c != keep && cand[c].alloc) (void)hipFree(cand[c].alloc);
+    for (void* sp : spacers) (void)hipFree(sp);
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
   };
@@ -752,8 +758,22 @@ int place_state_impl(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidate
       (void)hipGetLastError();
       break;
     }
-    if (static_cast<int64_t>(free_b) < bytes + kReserve) break;
-    if (max_extra_bytes > 0 && extra + bytes > max_extra_bytes) break;
+    const int64_t gap = bytes < kStride ? kStride - bytes : 0;
+    if (static_cast<int64_t>(free_b) < gap + bytes + kReserve) break;
+    if (max_extra_bytes > 0 && extra + gap + bytes > max_extra_bytes) break;
+    bool spaced = true;
+    for (int64_t done = 0; done < gap && spaced; done += kSpacerPiece) {
+      void* sp = nullptr;
+      const int64_t piece = gap - done < kSpacerPiece ? gap - done : kSpacerPiece;
+      if (hipMalloc(&sp, static_cast<size_t>(piece)) != hipSuccess) {
+        (void)hipGetLastError();
+        spaced = false;
+      } else {
+        spacers.push_back(sp);
+        extra += piece;
+      }
+    }
+    if (!spaced) break;
     Candidate c;
     if (alloc_state_block(ctx, &c.alloc, &c.ptrs) != GAC_OK) break;  // out of memory: stop quietly
     extra += bytes;

@@ -470,7 +470,7 @@ def test_state_placement_preserves_contents_and_results():
     ctx = B.Gac(numel, B.BF16)
     ctx.gac_state_import(d0, 0)
     g_before = U.clone_list(g)
-    rep = ctx.gac_place_state(g, 4, max_extra_bytes=2 << 30)
+    rep = ctx.gac_place_state(g, 4, max_extra_bytes=40 << 30)
     torch.cuda.synchronize()
     assert 1 <= rep.n_candidates <= 4 and 0 <= rep.chosen < rep.n_candidates
     assert all(rep.probe_ms[i] > 0 for i in range(rep.n_candidates))
