@@ -464,32 +464,40 @@ def test_state_placement_preserves_contents_and_results():
     assert (rep.n_candidates, rep.chosen) == (1, 0)
     ctx.close()
 
-    big = [(8192, 8192), (8192, 8192), (5, 7), (8192, 8200)]       # ~400 MiB: above the limit
+    for dtype, code, big, off in ((torch.bfloat16, B.BF16, [(8192, 8192), (8192, 8192), (5, 7), (8192, 8200)], 0),
+                                  (torch.float32, B.F32, [(4096, 8192), (8192, 4100), (3,), (4096, 8192)], 0),
+                                  (torch.bfloat16, B.BF16, [(8192, 8192), (8192, 8200), (11,)], 3)):
+        numel = [W.numel(x) for x in big]                 # 256-400 MiB: above the limit
+        g0, d0 = W.correlated_pair(big, dtype, 0.15, 1e-3, config_id=42, device=DEV)
+        # gradients that start `off` elements into their allocation (views into flat buffers)
+        g = [torch.empty(n + 8, dtype=dtype, device=DEV)[off:off + n].view(x) for n, x in zip(numel, big)]
+        for a, b in zip(g, g0):
+            a.copy_(b)
+        ctx = B.Gac(numel, code)
+        ctx.gac_state_import(d0, 0)
+        g_before = U.clone_list(g)
+        rep = ctx.gac_place_state(g, 4, max_extra_bytes=40 << 30)
+        torch.cuda.synchronize()
+        assert 1 <= rep.n_candidates <= 4 and 0 <= rep.chosen < rep.n_candidates
+        assert all(rep.probe_ms[i] > 0 and rep.reduce_ms[i] > 0 for i in range(rep.n_candidates))
+        assert rep.apply_blocks in list(rep.blocks_tried[:rep.n_blocks_tried])
+        assert all(U.bits_equal(a, b) for a, b in zip(g, g_before)), "the probe must not change the gradients"
+        out = [torch.empty_like(t) for t in d0]
+        ctx.gac_state_export(out)
+        torch.cuda.synchronize()
+        assert all(U.bits_equal(a, b) for a, b in zip(out, d0)), "the state must survive the search"
+        # a step after the search against the oracle
+        g_h, d_h = U.host_copies(g), U.host_copies(d0)
+        res = ctx.gac_step(g)
+        torch.cuda.synchronize()
+        want, s, dec = O.step(g_h, d_h, code, 0.05, 0.3, 1e-8)
+        assert res.regime == dec.regime == B.PROJECT and abs(res.c - dec.c) <= U.COS_TOL
+        assert U.rel_l2(g, want) <= U.GRAD_TOL[code]
+        ctx.gac_state_export(out)
+        torch.cuda.synchronize()
+        assert all(U.bits_equal(a, b) for a, b in zip(out, g_before))
+        ctx.close()
     numel = [W.numel(x) for x in big]
-    g, d0 = W.correlated_pair(big, dtype, 0.15, 1e-3, config_id=42, device=DEV)
-    ctx = B.Gac(numel, B.BF16)
-    ctx.gac_state_import(d0, 0)
-    g_before = U.clone_list(g)
-    rep = ctx.gac_place_state(g, 4, max_extra_bytes=40 << 30)
-    torch.cuda.synchronize()
-    assert 1 <= rep.n_candidates <= 4 and 0 <= rep.chosen < rep.n_candidates
-    assert all(rep.probe_ms[i] > 0 for i in range(rep.n_candidates))
-    assert rep.apply_blocks in list(rep.blocks_tried[:rep.n_blocks_tried])
-    assert all(U.bits_equal(a, b) for a, b in zip(g, g_before)), "the probe must not change the gradients"
-    out = [torch.empty_like(t) for t in d0]
-    ctx.gac_state_export(out)
-    torch.cuda.synchronize()
-    assert all(U.bits_equal(a, b) for a, b in zip(out, d0)), "the state must survive the move"
-    # a step after the move against the oracle
-    g_h, d_h = U.host_copies(g), U.host_copies(d0)
-    res = ctx.gac_step(g)
-    torch.cuda.synchronize()
-    want, s, dec = O.step(g_h, d_h, B.BF16, 0.05, 0.3, 1e-8)
-    assert res.regime == dec.regime == B.PROJECT and abs(res.c - dec.c) <= U.COS_TOL
-    assert U.rel_l2(g, want) <= U.GRAD_TOL[B.BF16]
-    ctx.gac_state_export(out)
-    torch.cuda.synchronize()
-    assert all(U.bits_equal(a, b) for a, b in zip(out, g_before))
     # a caller-provided state cannot be moved
     ctx2 = B.Gac(numel, B.BF16, state=[torch.zeros_like(t) for t in g])
     with pytest.raises(B.GacError) as e:
