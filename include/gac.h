@@ -223,7 +223,7 @@ int gac_reset(gac_ctx* ctx, void* hip_stream);
  * max_candidates - 1 further allocations of the same size, which are held until the end (with
  * spacer allocations between them when the state is smaller than 12 GiB) so that each lands
  * at least 12 GiB deeper in memory than the one before (the search ends early once a location
- * 3 % better than the first has been followed by two that are no better); it then moves the state (contents
+ * 3 % better than the first has been followed by two that are no better, or after eight in a row without gain); it then moves the state (contents
  * preserved bit for bit) to the location with the smallest sum of the two, frees the rest, and picks the workgroup
  * count of the in-place pass the same way (unless gac_config.apply_blocks fixed it).
  *   grad_ptrs        the gradient buffers the steps will use (contents preserved bit for bit;

@@ -747,12 +747,14 @@ int place_state_impl(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidate
                           &rep->reduce_ms[0]);
   int64_t extra = 0;
   // The search ends early once a clearly better location (3 %) has been followed by two
-  // that are no better: every candidate is memory the driver has to take back afterwards.
+  // that are no better, or after eight in a row without any gain: every candidate is memory
+  // the driver has to take back afterwards.
   double best_sum = rep->probe_ms[0] + rep->reduce_ms[0];
   const double first_sum = best_sum;
   int since_best = 0;
   while (rc == GAC_OK && static_cast<int>(cand.size()) < max_candidates) {
     if (since_best >= 2 && best_sum < 0.97 * first_sum) break;
+    if (since_best >= 8) break;  // a whole region (8 strides) without any gain: nothing to find
     size_t free_b = 0, total_b = 0;
     if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) {
       (void)hipGetLastError();
