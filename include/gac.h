@@ -237,8 +237,10 @@ int gac_reset(gac_ctx* ctx, void* hip_stream);
  *   report           optional; what was timed and what was chosen
  * Only for a state the library allocated (gac_config.state_ptrs == NULL), else
  * GAC_ERR_INVALID_ARG.  Lists under 256 MiB are left alone (they are not bandwidth bound).
- * Set-up time call: allocates, waits for the stream, cannot be captured into a graph.  The
- * driver clears freed device memory in the background, which takes HBM bandwidth for a few
+ * Set-up time call: allocates, waits for the stream, cannot be captured into a graph.  A
+ * graph of steps captured earlier keeps working (it reads the pointer table, which this call
+ * leaves on grad_ptrs and the final state) but keeps the workgroup count it was captured with.
+ * The driver clears freed device memory in the background, which takes HBM bandwidth for a few
  * seconds after the call (measured: ~4 % on the reduction pass for ~2.5 s per 100 GB freed). */
 #define GAC_MAX_PLACEMENT_CANDIDATES 16
 typedef struct gac_placement {

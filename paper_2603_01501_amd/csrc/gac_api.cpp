@@ -97,7 +97,10 @@ struct gac_ctx {
   bool state_is_callers = false;  // the state buffers were provided by the caller
 
   // pointer tables
-  Seg* dev_segs = nullptr;
+  Seg* dev_segs = nullptr;        // (gradient, state) per tensor: the table the step kernels read
+  Seg* dev_segs_state = nullptr;  // (source, destination) of state copies / zeroing: kept apart so
+                                  // that an export or import between two replays of a captured
+                                  // graph of steps cannot change what that graph reads
   AdamSeg* dev_adam = nullptr;
   Seg* pinned_segs[kPinnedSlots] = {};
   AdamSeg* pinned_adam[kPinnedSlots] = {};
@@ -178,6 +181,24 @@ int upload_segs(gac_ctx* ctx, const void* const* a, void* const* b, hipStream_t 
   GAC_HIP(ctx, hipMemcpyAsync(ctx->dev_segs, host, sizeof(Seg) * (n + 1), hipMemcpyHostToDevice, stream));
   GAC_HIP(ctx, hipEventRecord(ctx->slot_event[s], stream));
   ctx->segs_valid = true;
+  return GAC_OK;
+}
+
+// The table of a state operation (zero / copy); rare, so always uploaded.
+int upload_state_segs(gac_ctx* ctx, const void* const* a, void* const* b, hipStream_t stream) {
+  const int n = ctx->n_tensors;
+  const int s = ctx->slot;
+  ctx->slot = (s + 1) % kPinnedSlots;
+  GAC_HIP(ctx, hipEventSynchronize(ctx->slot_event[s]));
+  Seg* host = ctx->pinned_segs[s];
+  for (int j = 0; j <= n; ++j) {
+    host[j].a = (a && j < n) ? a[j] : nullptr;
+    host[j].b = j < n ? b[j] : nullptr;
+    host[j].numel = j < n ? ctx->numel[j] : 0;
+    host[j].first_chunk = ctx->first_chunk[j];
+  }
+  GAC_HIP(ctx, hipMemcpyAsync(ctx->dev_segs_state, host, sizeof(Seg) * (n + 1), hipMemcpyHostToDevice, stream));
+  GAC_HIP(ctx, hipEventRecord(ctx->slot_event[s], stream));
   return GAC_OK;
 }
 
@@ -298,9 +319,9 @@ DecideParams decide_params(const gac_ctx* ctx) {
 }
 
 int state_op(gac_ctx* ctx, int op, const void* const* src, void* const* dst, hipStream_t stream) {
-  int rc = upload_segs(ctx, src, dst, stream);
+  int rc = upload_state_segs(ctx, src, dst, stream);
   if (rc != GAC_OK) return rc;
-  GAC_HIP(ctx, gac::launch_state_op(ctx->dtype, op, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
+  GAC_HIP(ctx, gac::launch_state_op(ctx->dtype, op, ctx->dev_segs_state, ctx->n_chunks, ctx->chunk_elems,
                                     ctx->grid_state, stream));
   return GAC_OK;
 }
@@ -467,6 +488,7 @@ int init_impl(gac_ctx** out, const gac_config* cfg) {
   if (rc != GAC_OK) return rc;
 
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_segs), sizeof(Seg) * (n + 1)));
+  GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_segs_state), sizeof(Seg) * (n + 1)));
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_adam), sizeof(AdamSeg) * (n > 0 ? n : 1)));
   for (int s = 0; s < kPinnedSlots; ++s) {
     GAC_HIP(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned_segs[s]), sizeof(Seg) * (n + 1), hipHostMallocDefault));
@@ -514,6 +536,7 @@ void gac_destroy(gac_ctx* ctx) {
     (void)hipDeviceSynchronize();
     if (ctx->state_alloc) (void)hipFree(ctx->state_alloc);
     if (ctx->dev_segs) (void)hipFree(ctx->dev_segs);
+    if (ctx->dev_segs_state) (void)hipFree(ctx->dev_segs_state);
     if (ctx->dev_adam) (void)hipFree(ctx->dev_adam);
     if (ctx->dev_partials) (void)hipFree(ctx->dev_partials);
     if (ctx->dev_sums) (void)hipFree(ctx->dev_sums);
@@ -847,8 +870,13 @@ int place_state_impl(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidate
     if (rc == GAC_OK) ctx->grid_apply = best_blocks;
   }
   rep->apply_blocks = ctx->grid_apply;
-  cleanup(best);
+  // Leave the device pointer table on (grad_ptrs, final state): a graph captured earlier reads
+  // the table when it is replayed and must never see a candidate that is about to be freed.
   ctx->segs_valid = false;
+  if (rc == GAC_OK) rc = upload_segs(ctx, const_cast<const void* const*>(grad_ptrs), ctx->state.data(), stream);
+  if (rc == GAC_OK && hipStreamSynchronize(stream) != hipSuccess)
+    rc = fail_hip(ctx, hipGetLastError(), "hipStreamSynchronize");
+  cleanup(best);
   return rc;
 }
 }  // namespace

@@ -205,6 +205,50 @@ def test_seven_billion_bf16_list_consecutive_steps():
     ctx.close()
 
 
+def test_graph_captured_before_placement_survives_the_move():
+    """1.5B-style bf16 list: a HIP graph of the asynchronous step is captured, then
+    gac_place_state moves the state (on an otherwise empty device it does; the checks hold
+    either way), then the graph is replayed: it must act on the state's new location and give
+    bit for bit what an eager, unplaced context gives on the same inputs."""
+    dtype = torch.bfloat16
+    shapes = W.MODEL_15B.tensor_shapes()
+    numel = [W.numel(s) for s in shapes]
+    stream = W.AR1Stream(shapes, dtype, 0.15, 1e-3, config_id=33, device=DEV)
+    g = [torch.empty(s, dtype=dtype, device=DEV) for s in shapes]
+    ctx = B.Gac(numel, B.BF16)
+    ref = B.Gac(numel, B.BF16)
+    stream.next_into(g)
+    ctx.gac_step(g, sync=False)                     # eager: uploads the pointer table
+    ref.gac_step(U.clone_list(g))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        ctx.gac_step(g, stream=torch.cuda.current_stream(), sync=False)
+    torch.cuda.synchronize()
+    rep = ctx.gac_place_state(g)
+    say(f"placement: {rep.n_candidates} locations timed, chose {rep.chosen}")
+    state = [torch.empty_like(t) for t in g]
+    for i in range(3):
+        stream.next_into(g)
+        g_in = U.clone_list(g)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        g_ref = U.clone_list(g_in)
+        r = ref.gac_step(g_ref)
+        torch.cuda.synchronize()
+        assert r.regime == B.PROJECT
+        assert all(U.bits_equal(a, b) for a, b in zip(g, g_ref)), f"replay {i}: projected gradient"
+        ctx.gac_state_export(state)
+        torch.cuda.synchronize()
+        assert all(U.bits_equal(a, b) for a, b in zip(state, g_in)), f"replay {i}: state"
+    c_hist, r_hist, first = ctx.gac_history_read()
+    assert len(c_hist) == 4 and r_hist[1:] == [B.PROJECT] * 3
+    ctx.close()
+    ref.close()
+
+
 def test_single_tensor_beyond_two_to_the_31_elements():
     """One bf16 tensor of 2^31 + 4099 elements (plus a small neighbour): element offsets inside
     a tensor need 64 bits; the tail chunk is ragged and not a multiple of the vector width."""
