@@ -749,22 +749,38 @@ int place_state_impl(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidate
   const int64_t bytes = state_block_bytes(ctx);
   if (bytes < kMinBytes) return GAC_OK;
   GAC_HIP(ctx, hipStreamSynchronize(stream));
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  GAC_HIP(ctx, hipEventCreate(&e0));
-  if (hipEventCreate(&e1) != hipSuccess) {
-    (void)hipEventDestroy(e0);
-    return fail_hip(ctx, hipGetLastError(), "hipEventCreate");
-  }
-  std::vector<Candidate> cand(1);
+  // Everything the search holds; whatever is still here when it goes out of scope (also on
+  // an error or an exception) is released, except the candidate that became the state.
+  struct Search {
+    std::vector<Candidate> cand;
+    std::vector<void*> spacers;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int keep = -1;
+    ~Search() {
+      for (int c = 1; c < static_cast<int>(cand.size()); ++c)
+        if (c != keep && cand[c].alloc) (void)hipFree(cand[c].alloc);
+      for (void* sp : spacers) (void)hipFree(sp);
+      if (e0) (void)hipEventDestroy(e0);
+      if (e1) (void)hipEventDestroy(e1);
+    }
+  } search;
+  GAC_HIP(ctx, hipEventCreate(&search.e0));
+  GAC_HIP(ctx, hipEventCreate(&search.e1));
+  std::vector<Candidate>& cand = search.cand;
+  std::vector<void*>& spacers = search.spacers;
+  const hipEvent_t e0 = search.e0, e1 = search.e1;
+  cand.reserve(GAC_MAX_PLACEMENT_CANDIDATES);  // no reallocation between an allocation and its record
+  spacers.reserve(static_cast<size_t>(GAC_MAX_PLACEMENT_CANDIDATES * (kStride / kSpacerPiece)));
+  cand.resize(1);
   cand[0].alloc = ctx->state_alloc;
   cand[0].ptrs = ctx->state;
-  std::vector<void*> spacers;
-  auto cleanup = [&](int keep) {  // frees every candidate this call allocated except `keep`
-    for (int c = 1; c < static_cast<int>(cand.size()); ++c)
-      if (c != keep && cand[c].alloc) (void)hipFree(cand[c].alloc);
-    for (void* sp : spacers) (void)hipFree(sp);
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
+  // On any failure the pointer table goes back to (grad_ptrs, current state): a graph captured
+  // earlier must never replay against a candidate that has been freed.
+  auto fail = [&](int code) {
+    ctx->segs_valid = false;
+    (void)upload_segs(ctx, const_cast<const void* const*>(grad_ptrs), ctx->state.data(), stream);
+    (void)hipStreamSynchronize(stream);
+    return code;
   };
   int rc = time_candidate(ctx, grad_ptrs, cand[0].ptrs.data(), stream, e0, e1, &rep->probe_ms[0],
                           &rep->reduce_ms[0]);
@@ -814,11 +830,7 @@ int place_state_impl(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidate
       ++since_best;
     }
   }
-  if (rc != GAC_OK) {
-    cleanup(-1);
-    ctx->segs_valid = false;
-    return rc;
-  }
+  if (rc != GAC_OK) return fail(rc);
   rep->n_candidates = static_cast<int>(cand.size());
   auto both = [&](int c) { return rep->probe_ms[c] + rep->reduce_ms[c]; };
   int best = 0;
@@ -829,12 +841,9 @@ int place_state_impl(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidate
     rc = state_op(ctx, gac::kStateCopy, const_cast<const void* const*>(ctx->state.data()),
                   cand[best].ptrs.data(), stream);
     if (rc == GAC_OK && hipStreamSynchronize(stream) != hipSuccess) rc = fail_hip(ctx, hipGetLastError(), "hipStreamSynchronize");
-    if (rc != GAC_OK) {
-      cleanup(-1);
-      ctx->segs_valid = false;
-      return rc;
-    }
+    if (rc != GAC_OK) return fail(rc);
     (void)hipFree(ctx->state_alloc);
+    search.keep = best;
     ctx->state_alloc = cand[best].alloc;
     ctx->state = cand[best].ptrs;
   }
@@ -870,13 +879,13 @@ int place_state_impl(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidate
     if (rc == GAC_OK) ctx->grid_apply = best_blocks;
   }
   rep->apply_blocks = ctx->grid_apply;
+  if (rc != GAC_OK) return fail(rc);
   // Leave the device pointer table on (grad_ptrs, final state): a graph captured earlier reads
   // the table when it is replayed and must never see a candidate that is about to be freed.
   ctx->segs_valid = false;
-  if (rc == GAC_OK) rc = upload_segs(ctx, const_cast<const void* const*>(grad_ptrs), ctx->state.data(), stream);
+  rc = upload_segs(ctx, const_cast<const void* const*>(grad_ptrs), ctx->state.data(), stream);
   if (rc == GAC_OK && hipStreamSynchronize(stream) != hipSuccess)
     rc = fail_hip(ctx, hipGetLastError(), "hipStreamSynchronize");
-  cleanup(best);
   return rc;
 }
 }  // namespace
