@@ -235,8 +235,10 @@ int gac_reset(gac_ctx* ctx, void* hip_stream);
  *   max_extra_bytes  cap on the temporary device memory; 0 = whatever is free less a 4 GiB
  *                    reserve.  The search stops quietly when memory runs out.
  *   report           optional; what was timed and what was chosen
- * Only for a state the library allocated (gac_config.state_ptrs == NULL), else
- * GAC_ERR_INVALID_ARG.  Lists under 256 MiB are left alone (they are not bandwidth bound).
+ * A state the caller provided (gac_config.state_ptrs) cannot be moved: then max_candidates
+ * must be 1 (else GAC_ERR_INVALID_ARG), and the call times the two passes where the buffers
+ * are (report->probe_ms[0], reduce_ms[0]: what a caller needs to compare placements of its own)
+ * and tunes the workgroup count.  Lists under 256 MiB are left alone (not bandwidth bound).
  * Set-up time call: allocates, waits for the stream, cannot be captured into a graph.  A
  * graph of steps captured earlier keeps working (it reads the pointer table, which this call
  * leaves on grad_ptrs and the final state) but keeps the workgroup count it was captured with.

@@ -892,8 +892,8 @@ int place_state_impl(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidate
 
 int gac_place_state(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidates,
                     int64_t max_extra_bytes, void* hip_stream, gac_placement* report) {
-  if (ctx == nullptr || ctx->state_is_callers || max_candidates < 1 ||
-      max_candidates > GAC_MAX_PLACEMENT_CANDIDATES || max_extra_bytes < 0)
+  if (ctx == nullptr || max_candidates < 1 || max_candidates > GAC_MAX_PLACEMENT_CANDIDATES ||
+      max_extra_bytes < 0 || (ctx->state_is_callers && max_candidates != 1))
     return GAC_ERR_INVALID_ARG;
   int rc = check_ptrs(ctx, const_cast<const void* const*>(grad_ptrs));
   if (rc == GAC_OK) rc = check_not_state(ctx, grad_ptrs);

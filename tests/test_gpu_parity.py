@@ -498,8 +498,15 @@ def test_state_placement_preserves_contents_and_results():
         assert all(U.bits_equal(a, b) for a, b in zip(out, g_before))
         ctx.close()
     numel = [W.numel(x) for x in big]
-    # a caller-provided state cannot be moved
-    ctx2 = B.Gac(numel, B.BF16, state=[torch.zeros_like(t) for t in g])
+    # a caller-provided state cannot be moved, only measured where it is
+    mine = [torch.zeros_like(t) for t in g]
+    ctx2 = B.Gac(numel, B.BF16, state=mine)
     with pytest.raises(B.GacError) as e:
         ctx2.gac_place_state(g, 2)
     assert e.value.code == B.ERR_INVALID_ARG
+    g_before = U.clone_list(g)
+    rep = ctx2.gac_place_state(g, 1)
+    assert (rep.n_candidates, rep.chosen) == (1, 0) and rep.probe_ms[0] > 0 and rep.reduce_ms[0] > 0
+    assert rep.apply_blocks in list(rep.blocks_tried[:rep.n_blocks_tried])
+    assert all(U.bits_equal(a, b) for a, b in zip(g, g_before))
+    assert all(float(t.abs().max()) == 0.0 for t in mine if t.numel())
