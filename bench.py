@@ -12,6 +12,13 @@ so that the projection branch (the full 6 N s bytes: cosine + projection + state
 runs; the same workload under the paper's default thresholds (0.05, 0.3), where such aligned
 gradients are skipped (4 N s bytes), is reported in "paper_default_thresholds".
 
+Set-up, not timed: after the first steps the library is asked to place its state buffer
+(gac_place_state: it times both passes with the state at successive allocations and keeps the
+fastest; on MI355X two buffers in different thirds of HBM run the in-place pass ~14 % faster),
+then steps run until the step time is steady, because the driver clears the memory the search
+freed in the background for a few seconds.  "state_placement" in the output holds what was
+timed and chosen and the step time before it; --no-placement skips it.
+
 Prints ONE JSON line.
 """
 from __future__ import annotations
