@@ -510,3 +510,63 @@ def test_state_placement_preserves_contents_and_results():
     assert rep.apply_blocks in list(rep.blocks_tried[:rep.n_blocks_tried])
     assert all(U.bits_equal(a, b) for a, b in zip(g, g_before))
     assert all(float(t.abs().max()) == 0.0 for t in mine if t.numel())
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_randomized_lists_against_the_oracle(seed):
+    """Seeded random tensor lists: number of tensors, sizes around the chunk and tile
+    boundaries, empty tensors, views that start 0-7 elements into their allocation, both
+    storage types, a non-default chunk size now and then, correlation drawn so that all three
+    regimes occur, state supplied by the caller or allocated by the library; two consecutive
+    steps, the second with the state the first one left."""
+    rng = np.random.default_rng(1000 + seed)
+    dtype = (torch.float32, torch.bfloat16)[seed % 2]
+    chunk = int(rng.choice([0, 0, 2048, 6144, 65536]))
+    edge = 16384 if dtype == torch.float32 else 32768
+    sizes = []
+    for _ in range(int(rng.integers(1, 9))):
+        kind = int(rng.integers(0, 6))
+        if kind == 0:
+            sizes.append(0)
+        elif kind == 1:
+            sizes.append(int(rng.integers(1, 40)))
+        elif kind == 2:
+            sizes.append(edge * int(rng.integers(1, 4)) + int(rng.integers(-9, 10)))
+        elif kind == 3:
+            sizes.append(edge * int(rng.integers(1, 6)))
+        else:
+            sizes.append(int(rng.integers(1, 300000)))
+    shapes = [(n,) for n in sizes]
+    rho = float(rng.choice([0.0, 0.02, 0.1, 0.2, -0.15, 0.6, -0.9]))
+    g0, d0 = W.correlated_pair(shapes, dtype, rho, 1e-3, config_id=500 + seed, device=DEV)
+    offs = [int(rng.integers(0, 8)) for _ in sizes]
+    g = [torch.empty(n + 8, dtype=dtype, device=DEV)[o:o + n] for n, o in zip(sizes, offs)]
+    for a, b in zip(g, g0):
+        a.copy_(b)
+    own_state = bool(rng.integers(0, 2))
+    d = [torch.empty(n + 8, dtype=dtype, device=DEV)[o:o + n] for n, o in zip(sizes, reversed(offs))] if own_state else None
+    ctx = B.Gac(sizes, U.code(dtype), state=d, chunk_elems=chunk)
+    ctx.gac_state_import(d0, 0)
+    g_raw = U.clone_list(g)
+    res = ctx.gac_step(g)
+    torch.cuda.synchronize()
+    state = [torch.empty_like(t) for t in g0]
+    ctx.gac_state_export(state)
+    torch.cuda.synchronize()
+    U.check_step(res, g_raw, d0, g, state, dtype, C_LOW, C_HIGH, EPS)
+    if sum(sizes) > 0 and abs(rho) > 0.01:
+        assert abs(res.c - rho) <= 5 * (1 - rho * rho) / math.sqrt(sum(sizes)) + 3e-3
+    # second step: new gradient, reference = what the first step stored
+    g2, _ = W.correlated_pair(shapes, dtype, 0.0, 1e-3, config_id=900 + seed, device=DEV)
+    mix = float(rng.choice([0.0, 0.1, 0.25, 0.5]))
+    for a, b, r in zip(g, g2, g_raw):
+        a.copy_((mix * r.float() + math.sqrt(1 - mix * mix) * b.float()).to(dtype))
+    g_raw2 = U.clone_list(g)
+    res2 = ctx.gac_step(g)
+    torch.cuda.synchronize()
+    state2 = [torch.empty_like(t) for t in g0]
+    ctx.gac_state_export(state2)
+    torch.cuda.synchronize()
+    U.check_step(res2, g_raw2, g_raw, g, state2, dtype, C_LOW, C_HIGH, EPS)
+    assert res2.step == 2
+    ctx.close()
