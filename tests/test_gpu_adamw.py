@@ -123,3 +123,27 @@ def test_safe_regime_is_plain_adamw():
     assert res.regime == B.SAFE and res.c == 0.0
     for a, q in zip(p, params):
         torch.testing.assert_close(a, q.detach(), rtol=2e-5, atol=1e-9)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_fused_adamw_on_randomized_lists(seed):
+    """Seeded random lists (sizes around the chunk edges, empty and tiny tensors), both storage
+    types, chunk size, step count, learning rate and regime drawn per seed."""
+    rng = np.random.default_rng(2000 + seed)
+    dtype = (torch.bfloat16, torch.float32)[seed % 2]
+    edge = 16384 if dtype == torch.float32 else 32768
+    sizes = []
+    for _ in range(int(rng.integers(1, 7))):
+        kind = int(rng.integers(0, 5))
+        sizes.append([0, int(rng.integers(1, 9)), edge * int(rng.integers(1, 3)) + int(rng.integers(-5, 6)),
+                      edge * int(rng.integers(1, 4)), int(rng.integers(1, 200000))][kind])
+    if sum(sizes) == 0:
+        sizes.append(4097)
+    shapes = [(n,) for n in sizes]
+    rho, c_high, expect = [(0.9, 2.0, B.PROJECT), (0.15, 0.3, B.PROJECT), (0.0, 0.3, B.SAFE),
+                           (0.9, 0.3, B.SKIP)][int(rng.integers(0, 4))]
+    if sum(sizes) < 5000 and expect != B.SKIP:
+        rho, c_high, expect = 0.9, 2.0, B.PROJECT      # short lists: keep c far from the thresholds
+    hyper = dict(PAPER, lr=float(rng.choice([1e-6, 1e-4, 3e-3])))
+    run_case(shapes, dtype, rho, c_high, hyper, int(rng.choice([1, 2, 17, 1000])), expect,
+             with_lowp=bool(rng.integers(0, 2)), chunk_elems=int(rng.choice([0, 2048, 8192])))
