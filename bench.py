@@ -24,7 +24,6 @@ Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
-import hashlib
 import json
 import os
 import sys
@@ -81,7 +80,7 @@ def recorded_traffic(kernel_src_sha):
         if ":" in line and not line.startswith("#"):
             k, v = line.split(":", 1)
             vals[k.strip()] = v.strip()
-    if vals.get("kernel_source_sha256") != kernel_src_sha:
+    if vals.get("kernel_code_sha256") != kernel_src_sha:
         return None
     try:
         return float(vals["traffic_bytes_per_launch"])
@@ -316,7 +315,7 @@ def main():
     ms_xs, res_xs = run_exchange(0.3, 1, n_x)
     assert res_xp.regime == B.PROJECT and res_xs.regime == B.SKIP
 
-    sha = hashlib.sha256(open(gac_build.SOURCES[0], "rb").read()).hexdigest()
+    sha = gac_build.kernel_code_sha256()
     apply_bytes = 4.0 * N * es
     achieved = apply_bytes / (ms_app * 1e-3) / 1e9
     out = {

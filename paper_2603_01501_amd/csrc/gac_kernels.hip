@@ -4,7 +4,10 @@
 //   pass 1 (reduce_kernel)   three inner products <g,d>, <g,g>, <d,d>      (Appendix A.1)
 //   finalize_kernel          cosine with eps, regime, alpha, coefficient    (Eq. 1, Sec. 4.2)
 //   pass 2 (apply_kernel)    g <- beta g + k d in place and d <- raw g      (Eq. 4, App. A.2)
-//          (apply_adamw_kernel: the same with AdamW consuming g' in registers, Table 2)
+//          (apply_adamw_kernel: the same with AdamW consuming g' in registers, Table 2;
+//           exchange_kernel: g' written over the old state, for callers that swap buffers)
+// Beside them: state_kernel (zero / copy of the state), diag_kernel and sweep_kernel (the
+// statistics of Table 3 and regime counts under other thresholds over the recorded c_t).
 // Both passes are bound by HBM bandwidth (3 FMA per 2 loaded elements, 1 FMA per 4 moved
 // elements), so there is no matrix-core work here; what matters is 16-byte accesses that
 // coalesce to full cache lines, many loads in flight per wave, and all CUs busy.
