@@ -15,7 +15,8 @@
 // Work distribution: the tensor list is cut into chunks (gac_internal.h: Seg); workgroup b
 // of a G-wide persistent grid takes chunks b, b+G, b+2G, ...  The chunk -> workgroup map is
 // static, every workgroup writes its own partial sums, and the finalize kernel adds them in
-// index order, so results are bit-reproducible.  No floating-point atomics anywhere.
+// a fixed order (lane j takes partials j, j+256, ...; then a fixed tree over lanes and
+// waves), so results are bit-reproducible.  No floating-point atomics anywhere.
 //
 // Accumulation: products are formed and summed in fp32 over one group of at most
 // GAC_REDUCE_UNROLL * 8 elements per lane (for bf16 inputs each product is exact in fp32), then the
@@ -67,9 +68,6 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #endif
 #ifndef GAC_REDUCE_NT_LOAD
 #define GAC_REDUCE_NT_LOAD 1
-#endif
-#ifndef GAC_REDUCE_DOT2
-#define GAC_REDUCE_DOT2 0
 #endif
 #ifndef GAC_APPLY_THREADS
 #define GAC_APPLY_THREADS 512
@@ -246,20 +244,6 @@ __device__ __forceinline__ void block_sum3(double (&s)[3]) {
 
 template <int DT>
 __device__ __forceinline__ void dot3(u32x4 a, u32x4 b, float& gd, float& gg, float& dd) {
-#if GAC_REDUCE_DOT2
-  if constexpr (DT == GAC_BF16) {
-    // two bf16 products and the running sum in one instruction per statistic
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const bf16x2 x = __builtin_bit_cast(bf16x2, a[i]);
-      const bf16x2 y = __builtin_bit_cast(bf16x2, b[i]);
-      gd = __builtin_amdgcn_fdot2_f32_bf16(x, y, gd, false);
-      gg = __builtin_amdgcn_fdot2_f32_bf16(x, x, gg, false);
-      dd = __builtin_amdgcn_fdot2_f32_bf16(y, y, dd, false);
-    }
-    return;
-  }
-#endif
   constexpr int N = Elem<DT>::kPerVec;
   float x[N], y[N];
   unpack<DT>(a, x);
@@ -488,143 +472,24 @@ __device__ __forceinline__ void apply_chunk_generic(const Chunk& ch, bool projec
   }
 }
 
-// Pass 2.  A workgroup of T lanes owns one chunk at a time.  A "whole tile" is an aligned
-// chunk of exactly T*U vectors per array (the default chunk size): each lane then holds U
-// vectors of g and of d in registers, so the whole chunk is read before any of it is
-// written, and the loads of the workgroup's NEXT whole tile are issued before the current
-// one is computed and stored (two register tiles), which keeps reads in flight during the
-// arithmetic and the stores.  Other chunks (tensor tails) take the generic path.
+// The traversal shared by the pass-2 kernels.  A workgroup of T lanes owns one chunk at a
+// time.  A "whole tile" is an aligned chunk of exactly T*U vectors per array (the default
+// chunk size): each lane then holds U vectors of each array in registers, so the whole chunk
+// is read before any of it is written, and the loads of the workgroup's NEXT whole tile are
+// issued before the current one is computed and stored (two register tiles), which keeps
+// reads in flight during the arithmetic and the stores.  Other chunks (tensor tails,
+// non-default chunk sizes) go to `generic`.
 //
 // Chunks are walked from the end of the list towards its start (the reduction pass has just
 // streamed the list front to back, so its last chunks would be the ones still cached).  With
 // the non-temporal loads of pass 1 this measured no different from a forward walk on 2-3 GB
 // lists; it is kept because it costs nothing.
-//
-// PROBE = true is the placement probe: the same loads, arithmetic and stores, but every value
-// is written back where it came from (g <- g, d <- d), so nothing changes; it is timed to
-// compare candidate locations of the state (gac_place_state).
-template <int DT, int T, int U, bool PROBE>
-__global__ __launch_bounds__(T) void apply_kernel(const Seg* __restrict__ segs,
-                                                         int n_tensors, int64_t n_chunks,
-                                                         int chunk_elems,
-                                                         const gac_result* __restrict__ res,
-                                                         float probe_k, float probe_beta) {
+template <int DT, int T, int U, typename Tile, typename Load, typename Store, typename Generic>
+__device__ __forceinline__ void walk_tiles(const Seg* __restrict__ segs, int n_tensors,
+                                           int64_t n_chunks, int chunk_elems, Load load_tile,
+                                           Store store_tile, Generic generic) {
   constexpr int N = Elem<DT>::kPerVec;
-  if (!PROBE && res->nonfinite) return;  // convention: a non-finite step modifies nothing
-  // g <- scale_g * g + coef_d * d when the step projects and/or clips, else g stays
-  const bool project = PROBE || res->modified != 0;
-  const float k = PROBE ? probe_k : static_cast<float>(res->coef_d);
-  const float beta = PROBE ? probe_beta : static_cast<float>(res->scale_g);
-  const int tid = threadIdx.x;
-
-  struct Tile {
-    u32x4 a[U], b[U];
-  };
-  auto whole = [&](const Chunk& ch) {
-    return ch.len == T * U * N;
-  };
-  auto load_tile = [&](const Chunk& ch, Tile& tl) {
-    const gvec* gv = reinterpret_cast<const gvec*>(ch.a) + tid;
-    const gvec* dv = reinterpret_cast<const gvec*>(ch.b) + tid;
-#pragma unroll
-    for (int u = 0; u < U; ++u) tl.a[u] = ld16<GAC_APPLY_NT_LOAD>(gv + u * T);
-    if (project) {
-#pragma unroll
-      for (int u = 0; u < U; ++u) tl.b[u] = ld16<GAC_APPLY_NT_LOAD>(dv + u * T);
-    }
-  };
-  auto store_tile = [&](const Chunk& ch, const Tile& tl) {
-    gvec* gv = reinterpret_cast<gvec*>(const_cast<gchar*>(ch.a)) + tid;
-    gvec* dv = reinterpret_cast<gvec*>(ch.b) + tid;
-    if (project) {
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const u32x4 r = project_vec<DT>(tl.a[u], tl.b[u], k, beta);
-        st16<GAC_APPLY_NT_STORE>(gv + u * T, PROBE ? same_or(r, tl.a[u]) : r);
-        st16<GAC_APPLY_NT_STORE>(dv + u * T, PROBE ? tl.b[u] : tl.a[u]);
-      }
-    } else {
-#pragma unroll
-      for (int u = 0; u < U; ++u) st16<GAC_APPLY_NT_STORE>(dv + u * T, tl.a[u]);
-    }
-  };
-
-  int t = n_tensors - 1;
-  int64_t cr = blockIdx.x;
-  if (cr >= n_chunks) return;
-  Chunk cur = locate<true>(segs, t, n_chunks - 1 - cr, chunk_elems, Elem<DT>::kSize);
-  bool cur_whole = whole(cur);
-  Tile tc = {};
-  if (cur_whole) load_tile(cur, tc);
-  for (;;) {
-    cr += gridDim.x;
-    const bool more = cr < n_chunks;
-    Chunk next = cur;
-    bool next_whole = false;
-    Tile tn = {};
-    if (more) {
-      next = locate<true>(segs, t, n_chunks - 1 - cr, chunk_elems, Elem<DT>::kSize);
-      next_whole = whole(next);
-      if (next_whole) load_tile(next, tn);
-    }
-    if (cur_whole) {
-      store_tile(cur, tc);
-    } else {
-      apply_chunk_generic<DT, T, U, PROBE>(cur, project, k, beta);
-    }
-    if (!more) break;
-    cur = next;
-    cur_whole = next_whole;
-    tc = tn;
-  }
-}
-
-// Pass 2 of the buffer-exchange form: the gradient for the optimizer is written over the OLD
-// reference state (which nobody needs after this step) and g itself is left alone, because
-// the caller hands the g buffers over as the new reference state.  When the step projects
-// (or clips): read g, read d, write g' (3 N s bytes); otherwise there is nothing to move.
-template <int DT, int T, int U>
-__global__ __launch_bounds__(T) void exchange_kernel(const Seg* __restrict__ segs,
-                                                            int n_tensors, int64_t n_chunks,
-                                                            int chunk_elems,
-                                                            const gac_result* __restrict__ res) {
-  constexpr int N = Elem<DT>::kPerVec;
-  if (res->nonfinite || !res->modified) return;
-  const float k = static_cast<float>(res->coef_d);
-  const float beta = static_cast<float>(res->scale_g);
-  const int tid = threadIdx.x;
-
-  struct Tile {
-    u32x4 a[U], b[U];
-  };
-  auto whole = [&](const Chunk& ch) {
-    return ch.len == T * U * N;
-  };
-  auto load_tile = [&](const Chunk& ch, Tile& tl) {
-    const gvec* gv = reinterpret_cast<const gvec*>(ch.a) + tid;
-    const gvec* dv = reinterpret_cast<const gvec*>(ch.b) + tid;
-#pragma unroll
-    for (int u = 0; u < U; ++u) tl.a[u] = ld16<GAC_APPLY_NT_LOAD>(gv + u * T);
-#pragma unroll
-    for (int u = 0; u < U; ++u) tl.b[u] = ld16<GAC_APPLY_NT_LOAD>(dv + u * T);
-  };
-  auto store_tile = [&](const Chunk& ch, const Tile& tl) {
-    gvec* dv = reinterpret_cast<gvec*>(ch.b) + tid;
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      st16<GAC_APPLY_NT_STORE>(dv + u * T, project_vec<DT>(tl.a[u], tl.b[u], k, beta));
-  };
-  auto generic = [&](const Chunk& ch) {
-    const gvec* gv = reinterpret_cast<const gvec*>(ch.a);
-    gvec* dv = reinterpret_cast<gvec*>(ch.b);
-    const int nvec = ch.len / N;
-    for (int i = tid; i < nvec; i += T)
-      st16<GAC_APPLY_NT_STORE>(dv + i, project_vec<DT>(ld16<GAC_APPLY_NT_LOAD>(gv + i),
-                                                       ld16<GAC_APPLY_NT_LOAD>(dv + i), k, beta));
-    for (int i = nvec * N + tid; i < ch.len; i += T)
-      store_elem<DT>(ch.b, i, fmaf(k, load_elem<DT>(ch.b, i), beta * load_elem<DT>(ch.a, i)));
-  };
-
+  auto whole = [&](const Chunk& ch) { return ch.len == T * U * N; };
   int t = n_tensors - 1;
   int64_t cr = blockIdx.x;
   if (cr >= n_chunks) return;
@@ -653,6 +518,105 @@ __global__ __launch_bounds__(T) void exchange_kernel(const Seg* __restrict__ seg
     cur_whole = next_whole;
     tc = tn;
   }
+}
+
+// Two register tiles' worth of one chunk of g and of d.
+template <int U>
+struct PairTile {
+  u32x4 a[U], b[U];
+};
+
+// Pass 2, in place: g <- scale_g g + coef_d d where the step projects and/or clips, d <- raw g.
+//
+// PROBE = true is the placement probe: the same loads, arithmetic and stores, but every value
+// is written back where it came from (g <- g, d <- d), so nothing changes; it is timed to
+// compare candidate locations of the state (gac_place_state).
+template <int DT, int T, int U, bool PROBE>
+__global__ __launch_bounds__(T) void apply_kernel(const Seg* __restrict__ segs,
+                                                         int n_tensors, int64_t n_chunks,
+                                                         int chunk_elems,
+                                                         const gac_result* __restrict__ res,
+                                                         float probe_k, float probe_beta) {
+  if (!PROBE && res->nonfinite) return;  // convention: a non-finite step modifies nothing
+  // g <- scale_g * g + coef_d * d when the step projects and/or clips, else g stays
+  const bool project = PROBE || res->modified != 0;
+  const float k = PROBE ? probe_k : static_cast<float>(res->coef_d);
+  const float beta = PROBE ? probe_beta : static_cast<float>(res->scale_g);
+  const int tid = threadIdx.x;
+
+  typedef PairTile<U> Tile;
+  auto load_tile = [&](const Chunk& ch, Tile& tl) {
+    const gvec* gv = reinterpret_cast<const gvec*>(ch.a) + tid;
+    const gvec* dv = reinterpret_cast<const gvec*>(ch.b) + tid;
+#pragma unroll
+    for (int u = 0; u < U; ++u) tl.a[u] = ld16<GAC_APPLY_NT_LOAD>(gv + u * T);
+    if (project) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) tl.b[u] = ld16<GAC_APPLY_NT_LOAD>(dv + u * T);
+    }
+  };
+  auto store_tile = [&](const Chunk& ch, const Tile& tl) {
+    gvec* gv = reinterpret_cast<gvec*>(const_cast<gchar*>(ch.a)) + tid;
+    gvec* dv = reinterpret_cast<gvec*>(ch.b) + tid;
+    if (project) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const u32x4 r = project_vec<DT>(tl.a[u], tl.b[u], k, beta);
+        st16<GAC_APPLY_NT_STORE>(gv + u * T, PROBE ? same_or(r, tl.a[u]) : r);
+        st16<GAC_APPLY_NT_STORE>(dv + u * T, PROBE ? tl.b[u] : tl.a[u]);
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < U; ++u) st16<GAC_APPLY_NT_STORE>(dv + u * T, tl.a[u]);
+    }
+  };
+
+  walk_tiles<DT, T, U, Tile>(segs, n_tensors, n_chunks, chunk_elems, load_tile, store_tile,
+                             [&](const Chunk& ch) { apply_chunk_generic<DT, T, U, PROBE>(ch, project, k, beta); });
+}
+
+// Pass 2 of the buffer-exchange form: the gradient for the optimizer is written over the OLD
+// reference state (which nobody needs after this step) and g itself is left alone, because
+// the caller hands the g buffers over as the new reference state.  When the step projects
+// (or clips): read g, read d, write g' (3 N s bytes); otherwise there is nothing to move.
+template <int DT, int T, int U>
+__global__ __launch_bounds__(T) void exchange_kernel(const Seg* __restrict__ segs,
+                                                            int n_tensors, int64_t n_chunks,
+                                                            int chunk_elems,
+                                                            const gac_result* __restrict__ res) {
+  constexpr int N = Elem<DT>::kPerVec;
+  if (res->nonfinite || !res->modified) return;
+  const float k = static_cast<float>(res->coef_d);
+  const float beta = static_cast<float>(res->scale_g);
+  const int tid = threadIdx.x;
+
+  typedef PairTile<U> Tile;
+  auto load_tile = [&](const Chunk& ch, Tile& tl) {
+    const gvec* gv = reinterpret_cast<const gvec*>(ch.a) + tid;
+    const gvec* dv = reinterpret_cast<const gvec*>(ch.b) + tid;
+#pragma unroll
+    for (int u = 0; u < U; ++u) tl.a[u] = ld16<GAC_APPLY_NT_LOAD>(gv + u * T);
+#pragma unroll
+    for (int u = 0; u < U; ++u) tl.b[u] = ld16<GAC_APPLY_NT_LOAD>(dv + u * T);
+  };
+  auto store_tile = [&](const Chunk& ch, const Tile& tl) {
+    gvec* dv = reinterpret_cast<gvec*>(ch.b) + tid;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      st16<GAC_APPLY_NT_STORE>(dv + u * T, project_vec<DT>(tl.a[u], tl.b[u], k, beta));
+  };
+  auto generic = [&](const Chunk& ch) {
+    const gvec* gv = reinterpret_cast<const gvec*>(ch.a);
+    gvec* dv = reinterpret_cast<gvec*>(ch.b);
+    const int nvec = ch.len / N;
+    for (int i = tid; i < nvec; i += T)
+      st16<GAC_APPLY_NT_STORE>(dv + i, project_vec<DT>(ld16<GAC_APPLY_NT_LOAD>(gv + i),
+                                                       ld16<GAC_APPLY_NT_LOAD>(dv + i), k, beta));
+    for (int i = nvec * N + tid; i < ch.len; i += T)
+      store_elem<DT>(ch.b, i, fmaf(k, load_elem<DT>(ch.b, i), beta * load_elem<DT>(ch.a, i)));
+  };
+
+  walk_tiles<DT, T, U, Tile>(segs, n_tensors, n_chunks, chunk_elems, load_tile, store_tile, generic);
 }
 
 // ------------------------------------------------------------------ pass 2 fused with AdamW
