@@ -570,3 +570,35 @@ def test_randomized_lists_against_the_oracle(seed):
     U.check_step(res2, g_raw2, g_raw, g, state2, dtype, C_LOW, C_HIGH, EPS)
     assert res2.step == 2
     ctx.close()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_thousands_of_tiny_tensors(dtype):
+    """4000 tensors of 0-60 elements plus a few large ones: every chunk is a tensor tail and
+    the chunk cursor crosses many tensors between two chunks of a workgroup."""
+    rng = np.random.default_rng(77)
+    sizes = [int(x) for x in rng.integers(0, 61, size=4000)]
+    for pos, n in ((10, 70001), (1999, 32768 * 3), (3990, 16384 * 2 + 5)):
+        sizes[pos] = n
+    shapes = [(n,) for n in sizes]
+    g, d0 = W.correlated_pair(shapes, dtype, 0.15, 1e-3, config_id=61, device=DEV)
+    ctx = B.Gac(sizes, U.code(dtype))
+    ctx.gac_state_import(d0, 0)
+    g_raw = U.clone_list(g)
+    res = ctx.gac_step(g)
+    torch.cuda.synchronize()
+    state = [torch.empty_like(t) for t in g]
+    ctx.gac_state_export(state)
+    torch.cuda.synchronize()
+    U.check_step(res, g_raw, d0, g, state, dtype, C_LOW, C_HIGH, EPS, expect_regime=B.PROJECT)
+    # the exchange form and the fused optimizer walk the same table
+    d = U.clone_list(d0)
+    ctx2 = B.Gac(sizes, U.code(dtype), state=d)          # init zeroes the state it is given
+    ctx2.gac_state_import(d0, 0)
+    mine = U.clone_list(g_raw)
+    res2, returned = ctx2.gac_step_exchange(mine)
+    torch.cuda.synchronize()
+    assert res2.regime == B.PROJECT and res2.c == res.c
+    assert all(U.bits_equal(a, b) for a, b in zip(returned, g)), "exchange form must give the same bits"
+    ctx.close()
+    ctx2.close()
