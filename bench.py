@@ -319,7 +319,8 @@ def main():
     apply_bytes = 4.0 * N * es
     achieved = apply_bytes / (ms_app * 1e-3) / 1e9
     out = {
-        "metric": "GAC step ms and achieved HBM GB/s (% of peak) on 7.6B-param bf16 gradient",
+        "metric": "GAC step ms and achieved HBM GB/s (% of peak) on 7.6B-param bf16 gradient"
+                  if args.workload == "7.6B" else f"GAC step ms and achieved HBM GB/s (% of peak) on {desc}",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
