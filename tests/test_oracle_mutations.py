@@ -34,6 +34,8 @@ MUTATIONS = [
     ("sweep_skip_exclusive", "else if (mag >= c_high) regime = ORACLE_SKIP;", "else if (mag > c_high) regime = ORACLE_SKIP;"),
     ("sweep_signed", "const double mag = std::fabs(c[step - 1]);", "const double mag = c[step - 1];"),
     ("sweep_burn_in_off_by_one", "for (int64_t step = burn_in + 1; step <= n; ++step) {", "for (int64_t step = burn_in; step <= n; ++step) {"),
+    ("sweep_counts_nonfinite_steps", "if (std::isnan(mag)) continue;", ""),
+    ("stats_count_nonfinite_steps", "if (!std::isnan(c[t])) a.push_back(std::fabs(c[t]));", "a.push_back(std::fabs(c[t]));"),
     ("adam_coupled_decay", "pi = pi - lr * weight_decay * pi;", "pi = pi - weight_decay * pi;"),
 ]
 
