@@ -49,6 +49,9 @@ def parse_args():
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--grid-blocks", type=int, default=0)
     ap.add_argument("--apply-blocks", type=int, default=0)
+    ap.add_argument("--free-gb", type=float, default=0.0,
+                    help="hold a ballast (2 GiB pieces) so that only this much device memory is free "
+                         "when the library is initialised: what gac_place_state can do next to a trainer")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the steps, run one plain copy of known size (gac_state_export of "
                          "the whole state: N*s bytes read, N*s written) so that a counter "
@@ -89,18 +92,38 @@ def recorded_traffic(kernel_src_sha):
 
 
 def timed_steps(ctx, stream, g, n_steps, torch):
-    """Runs n_steps GAC steps; returns (per-step wall ms list, last result)."""
+    """Runs n_steps GAC steps.  Returns (GPU ms per step, wall ms per step, last result): the
+    first from a pair of events recorded on the stream the library launches on, right before
+    and right after the call (the step as the GPU sees it: the reduction's first wave to the
+    in-place pass's last), the second from the host clock around the call and a device
+    synchronisation on both sides (adds the launch latency and the wake-up of the waiting host
+    thread)."""
     from paper_2603_01501_amd import binding as B
-    ms, res = [], None
+    gpu_ms, wall_ms, res = [], [], None
     g_ptrs = B.ptr_list(g)              # the gradient buffers do not move between steps
-    for _ in range(n_steps):
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(n_steps)]
+    for e0, e1 in events:
         stream.next_into(g)             # untimed: the next gradient of the AR(1) stream
         torch.cuda.synchronize()
         t0 = time.perf_counter()
+        e0.record()
         res = ctx.gac_step(g_ptrs)      # waits for the regime, like a training loop would
+        e1.record()
         torch.cuda.synchronize()
-        ms.append((time.perf_counter() - t0) * 1e3)
-    return ms, res
+        wall_ms.append((time.perf_counter() - t0) * 1e3)
+    gpu_ms = [e0.elapsed_time(e1) for e0, e1 in events]
+    return gpu_ms, wall_ms, res
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def cpu_baseline(shapes, dtype, torch):
@@ -135,7 +158,7 @@ def cpu_baseline(shapes, dtype, torch):
             "sample": f"one projection-regime step on the first {len(take)} tensors of the list "
                       f"({n} elements), mean of {reps} runs, {dt:.1f} s each, single-threaded",
             "ms_per_step_extrapolated": dt * 1e3 * (sum(W.numel(s) for s in shapes) / n),
-            "host_cpus": os.cpu_count()}
+            "host_cpus": os.cpu_count(), "cpu_model": cpu_model()}
 
 
 def main_adamw(args):
@@ -229,13 +252,26 @@ def main():
     N = sum(numel)
     es = 2 if dtype == torch.bfloat16 else 4
     code = B.torch_dtype_code(dtype)
+    storage = str(dtype).split(".")[-1]
+    GiB = float(2 ** 30)
 
     stream = W.AR1Stream(shapes, dtype, 0.95, 1e-3, config_id=config_id, device="cuda:0")
     g = [torch.empty(s, dtype=dtype, device="cuda:0") for s in shapes]
 
-    placement = {}
+    # --free-gb: what a trainer's parameters, optimizer state and activations would leave.  The
+    # ballast is taken in 2 GiB pieces before the library allocates anything.
+    ballast = []
+    if args.free_gb > 0:
+        torch.cuda.synchronize()
+        free_now = torch.cuda.mem_get_info()[0]
+        take = free_now - int(args.free_gb * GiB)
+        while take > 0:
+            piece = min(take, 2 * 2 ** 30)
+            ballast.append(torch.empty(piece, dtype=torch.uint8, device="cuda:0"))
+            take -= piece
+    free_at_init = torch.cuda.mem_get_info()[0]
 
-    def settle(ctx, freed_bytes, limit_s=20.0):
+    def settle(ctx, strm, freed_bytes, limit_s=20.0):
         """Untimed: steps until the step time is steady.  After large frees (the placement
         search) the driver clears the freed device memory in the background, which takes HBM
         bandwidth from whatever runs meanwhile: measured ~2.5 s per 100 GB, so wait at least
@@ -244,7 +280,7 @@ def main():
         min_s = 1.0 + 4.0 * freed_bytes / 100e9
         prev = None
         while time.perf_counter() - t0 < limit_s:
-            ms, _ = timed_steps(ctx, stream, g, 4, torch)
+            ms, _, _ = timed_steps(ctx, strm, g, 4, torch)
             cur = min(ms)
             steady = prev is not None and abs(cur - prev) <= 0.003 * prev
             if steady and time.perf_counter() - t0 >= min_s:
@@ -252,67 +288,114 @@ def main():
             prev = cur
             time.sleep(0.25)
 
-    def run(c_high, warmup, steps):
-        ctx = B.Gac(numel, code, c_low=0.05, c_high=c_high, chunk_elems=args.chunk_elems,
-                    grid_blocks=args.grid_blocks, apply_blocks=args.apply_blocks)
-        # step 1 meets a zero reference and is always safe; it is part of the warm-up
-        timed_steps(ctx, stream, g, 1 + warmup, torch)
-        if not args.no_placement:
-            # set-up, not timed: the library measures where its state buffer is best kept
-            # relative to these gradient buffers (HBM rank effect) and moves it there
-            ms_before, _ = timed_steps(ctx, stream, g, 3, torch)
-            rep = ctx.gac_place_state(g)
-            placement[c_high] = {
-                "candidates_timed": rep.n_candidates, "chosen": rep.chosen,
-                "apply_probe_ms": [round(rep.probe_ms[i], 3) for i in range(rep.n_candidates)],
-                "reduce_ms": [round(rep.reduce_ms[i], 3) for i in range(rep.n_candidates)],
-                "apply_blocks": rep.apply_blocks,
-                "ms_per_step_before_placement": sum(ms_before) / len(ms_before)}
-            settle(ctx, (rep.n_candidates - 1) * max(float(N) * es, 12.0 * 2 ** 30))
-        ctx.gac_profile_enable(True)
-        ms, res = timed_steps(ctx, stream, g, steps, torch)
-        k_red, k_fin, k_app, n = ctx.gac_profile_read()
-        ctx.gac_profile_enable(False)
-        if args.calibration_copy:
-            ctx.gac_state_export(g)
-            torch.cuda.synchronize()
-        ctx.close()
-        torch.cuda.empty_cache()
-        return ms, res, (k_red / n, k_fin / n, k_app / n)
+    def summary(ms):
+        return {"mean": sum(ms) / len(ms), "min": min(ms), "median": sorted(ms)[len(ms) // 2]}
 
-    ms, res, (ms_red, ms_fin, ms_app) = run(2.0, args.warmup, args.steps)
-    assert res.regime == B.PROJECT, f"expected the projection regime, got {res.regime} (c={res.c})"
-    ms_step = sum(ms) / len(ms)
-    step_bytes = 6.0 * N * es
-    value = step_bytes / (ms_step * 1e-3) / 1e9
+    def measure(ctx, strm, steps, want_regime, bytes_per_step, kernel_split=True):
+        """`steps` timed steps with nothing but the step in the stream, then (kernel_split) as
+        many again with the library's per-kernel events switched on."""
+        gpu_ms, wall_ms, res = timed_steps(ctx, strm, g, steps, torch)
+        assert res.regime == want_regime, f"expected regime {want_regime}, got {res.regime} (c={res.c})"
+        out = {"regime": B.REGIME_NAMES[res.regime], "cosine": res.c,
+               "ms_per_step": summary(gpu_ms)["mean"], "ms_per_step_min": min(gpu_ms),
+               "ms_per_step_median": summary(gpu_ms)["median"], "ms_per_step_wall": summary(wall_ms)["mean"],
+               "bytes_per_step": bytes_per_step,
+               "GBps": bytes_per_step / summary(gpu_ms)["mean"] / 1e6}
+        if kernel_split:
+            ctx.gac_profile_enable(True)
+            timed_steps(ctx, strm, g, steps, torch)
+            k_red, k_fin, k_app, n = ctx.gac_profile_read()
+            ctx.gac_profile_enable(False)
+            out["kernel_ms"] = {"reduce": k_red / n, "apply": k_app / n}
+        return out
+
+    # ---- one context for the in-place form: first steps, placement, then every threshold pair
+    ctx = B.Gac(numel, code, c_low=0.05, c_high=2.0, chunk_elems=args.chunk_elems,
+                grid_blocks=args.grid_blocks, apply_blocks=args.apply_blocks)
+    # step 1 meets a zero reference and is always safe; it is part of the warm-up
+    timed_steps(ctx, stream, g, 1 + args.warmup, torch)
+    placement = None
+    if not args.no_placement:
+        # set-up, not timed: the library measures where its state buffer is best kept relative
+        # to these gradient buffers (HBM rank effect) and moves it there
+        ms_before, _, _ = timed_steps(ctx, stream, g, 3, torch)
+        rep = ctx.gac_place_state(g)
+        placement = {
+            "what": "gac_place_state: set-up call that times the two passes with the state at successive "
+                    "allocations and keeps the fastest (gradients and state in different thirds of HBM run "
+                    "the in-place pass ~10 % faster)",
+            "candidates_timed": rep.n_candidates, "chosen": rep.chosen,
+            "apply_probe_ms": [round(rep.probe_ms[i], 3) for i in range(rep.n_candidates)],
+            "reduce_ms": [round(rep.reduce_ms[i], 3) for i in range(rep.n_candidates)],
+            "apply_blocks": rep.apply_blocks,
+            "bytes_held_peak": rep.bytes_held_peak,
+            "free_bytes_before_gac_init": free_at_init,
+            "ms_per_step_before_placement": sum(ms_before) / len(ms_before)}
+        settle(ctx, stream, float(rep.bytes_held_peak))
+    else:
+        timed_steps(ctx, stream, g, args.warmup, torch)
+
+    # headline: projection regime, 6 N s bytes
+    head = measure(ctx, stream, args.steps, B.PROJECT, 6.0 * N * es)
+    ms_step = head["ms_per_step"]
+    value = head["GBps"]
+    ms_red, ms_app = head["kernel_ms"]["reduce"], head["kernel_ms"]["apply"]
+
+    # the same gradients under the paper's thresholds (Appendix C): aligned like this they are skipped
+    n_side = max(3, min(8, args.steps))
+    ctx.gac_set_thresholds(0.05, 0.3)
+    skip = measure(ctx, stream, n_side, B.SKIP, 4.0 * N * es)
+    if args.calibration_copy:
+        ctx.gac_state_export(g)
+        torch.cuda.synchronize()
+
+    # consecutive gradients with correlation 0.15: inside the paper's projection band, so the
+    # projection kernel runs with the paper's own thresholds
+    del stream
+    torch.cuda.empty_cache()
+    stream15 = W.AR1Stream(shapes, dtype, 0.15, 1e-3, config_id=config_id + 20, device="cuda:0")
+    timed_steps(ctx, stream15, g, 2, torch)  # the first one meets the other stream's last gradient
+    rho015 = measure(ctx, stream15, n_side, B.PROJECT, 6.0 * N * es)
+    ctx.close()
+    torch.cuda.empty_cache()
+
+    # ---- snapshot form: two library-owned state buffers, the snapshot written by pass 1
+    snap = B.Gac(numel, code, c_low=0.05, c_high=0.3, chunk_elems=args.chunk_elems,
+                 grid_blocks=args.grid_blocks, apply_blocks=args.apply_blocks,
+                 flags=B.FLAG_SNAPSHOT_IN_REDUCE)
+    timed_steps(snap, stream15, g, 3, torch)
+    snap_proj = measure(snap, stream15, n_side, B.PROJECT, 6.0 * N * es)
+    snap.gac_set_thresholds(0.2, 0.3)      # |c| = 0.15 <= c_low: the safe regime
+    snap_safe = measure(snap, stream15, n_side, B.SAFE, 3.0 * N * es)
+    snap.close()
+    del stream15
+    torch.cuda.empty_cache()
+    stream = W.AR1Stream(shapes, dtype, 0.95, 1e-3, config_id=config_id, device="cuda:0")
 
     def run_exchange(c_high, warmup, steps):
         """The same steps through gac_step_exchange: buffers change hands, no snapshot copy."""
         state = [torch.zeros(s, dtype=dtype, device="cuda:0") for s in shapes]
-        ctx = B.Gac(numel, code, c_low=0.05, c_high=c_high, state=state, chunk_elems=args.chunk_elems,
-                    grid_blocks=args.grid_blocks, apply_blocks=args.apply_blocks)
+        xctx = B.Gac(numel, code, c_low=0.05, c_high=c_high, state=state, chunk_elems=args.chunk_elems,
+                     grid_blocks=args.grid_blocks, apply_blocks=args.apply_blocks)
         mine, ms, res = g, [], None
         for i in range(1 + warmup + steps):
             stream.next_into(mine)
             torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            res, mine = ctx.gac_step_exchange(mine)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            res, mine = xctx.gac_step_exchange(mine)
+            e1.record()
             torch.cuda.synchronize()
             if i > warmup:
-                ms.append((time.perf_counter() - t0) * 1e3)
-        ctx.close()
+                ms.append(e0.elapsed_time(e1))
+        xctx.close()
         del state, mine
         torch.cuda.empty_cache()
         return ms, res
 
-    ms_d, res_d, (d_red, d_fin, d_app) = run(0.3, 1, max(3, min(5, args.steps)))
-    assert res_d.regime == B.SKIP
-    ms_step_d = sum(ms_d) / len(ms_d)
-
-    n_x = max(3, min(8, args.steps))
-    ms_xp, res_xp = run_exchange(2.0, 1, n_x)
+    ms_xp, res_xp = run_exchange(2.0, 1, n_side)
     g = [torch.empty(s, dtype=dtype, device="cuda:0") for s in shapes]  # the old ones changed hands
-    ms_xs, res_xs = run_exchange(0.3, 1, n_x)
+    ms_xs, res_xs = run_exchange(0.3, 1, n_side)
     assert res_xp.regime == B.PROJECT and res_xs.regime == B.SKIP
 
     sha = gac_build.kernel_code_sha256()
@@ -323,30 +406,37 @@ def main():
                   if args.workload == "7.6B" else f"GAC step ms and achieved HBM GB/s (% of peak) on {desc}",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32", "storage_dtype": storage, "data": "synthetic",
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
-        "config": {"workload": f"{desc}, N={N}, {str(dtype).split('.')[-1]} storage, AR(1) phi=0.95, "
+        "timing": "value, ms_per_step and pct_of_hbm_peak are WHOLE-STEP figures (6*N*s bytes over the time "
+                  "between two events on the library's stream around gac_step, mean of the timed steps); "
+                  "ms_per_step_wall is the host clock around the same call with a device synchronisation "
+                  "on both sides; roofline.* is for ONE kernel (the in-place pass), timed in a second loop "
+                  "of the same length with the library's per-kernel events on",
+        "config": {"workload": f"{desc}, N={N}, {storage} storage, AR(1) phi=0.95, "
                                "thresholds (0.05, 2.0): projection regime, 6*N*s bytes per step",
-                   "n_tensors": len(shapes), "numel": N, "bytes_per_step": step_bytes,
-                   "cosine": res.c, "regime": B.REGIME_NAMES[res.regime],
-                   "ms_per_step_min": min(ms), "ms_per_step_median": sorted(ms)[len(ms) // 2]},
+                   "n_tensors": len(shapes), "numel": N, "bytes_per_step": 6.0 * N * es,
+                   "cosine": head["cosine"], "regime": head["regime"],
+                   "ms_per_step_min": head["ms_per_step_min"], "ms_per_step_median": head["ms_per_step_median"],
+                   "ms_per_step_wall": head["ms_per_step_wall"],
+                   "free_gb_requested": args.free_gb if args.free_gb > 0 else None},
         "roofline": {"bound": "hbm", "kernel": "apply_kernel (projection + state update)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": recorded_traffic(sha),
                      "algorithmic_bytes_per_launch": apply_bytes, "avg_launch_ms": ms_app},
-        "kernels": {"reduce_kernel": {"avg_ms": ms_red, "bytes": 2.0 * N * es,
-                                      "GBps": 2.0 * N * es / (ms_red * 1e-3) / 1e9},
-                    "finalize_kernel": {"avg_ms": ms_fin},
+        "kernels": {"reduce_kernel (with the finalize step in its last workgroup)":
+                        {"avg_ms": ms_red, "bytes": 2.0 * N * es, "GBps": 2.0 * N * es / (ms_red * 1e-3) / 1e9},
                     "apply_kernel": {"avg_ms": ms_app, "bytes": apply_bytes, "GBps": achieved}},
-        "state_placement": {"what": "gac_place_state: set-up call that times the two passes with the state at "
-                                    "successive allocations and keeps the fastest (gradients and state in "
-                                    "different thirds of HBM run the in-place pass ~10 % faster)",
-                            **({k: v for k, v in placement.get(2.0, {}).items()})} if placement else None,
-        "paper_default_thresholds": {"thresholds": [0.05, 0.3], "regime": B.REGIME_NAMES[res_d.regime],
-                                     "cosine": res_d.c, "ms_per_step": ms_step_d,
-                                     "bytes_per_step": 4.0 * N * es,
-                                     "GBps": 4.0 * N * es / (ms_step_d * 1e-3) / 1e9,
-                                     "reduce_ms": d_red, "apply_copy_ms": d_app},
+        "state_placement": placement,
+        "paper_default_thresholds": {"thresholds": [0.05, 0.3], **skip,
+                                     "what": "the same phi=0.95 gradients: skipped, reduction + state copy"},
+        "paper_default_thresholds_rho015": {"thresholds": [0.05, 0.3], **rho015,
+                                            "what": "AR(1) phi=0.15 gradients: projected under the paper's own thresholds"},
+        "snapshot_form": {"what": "GAC_FLAG_SNAPSHOT_IN_REDUCE: pass 1 writes the snapshot; a step that neither "
+                                  "projects nor clips has no pass 2 (state not placed: gac_place_state does "
+                                  "not cover this form)",
+                          "safe_phi015_thresholds_0.2_0.3": snap_safe,
+                          "projection_phi015_paper_thresholds": snap_proj},
         "exchange_form": {"what": "gac_step_exchange: the gradient buffers become the reference state and "
                                   "the old state buffers come back (holding g' when projected)",
                           "projection": {"ms_per_step": sum(ms_xp) / len(ms_xp), "bytes_per_step": 5.0 * N * es,
@@ -355,6 +445,7 @@ def main():
                                                             "bytes_per_step": 2.0 * N * es,
                                                             "GBps": 2.0 * N * es / (sum(ms_xs) / len(ms_xs)) / 1e6}},
     }
+    del ballast
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shapes, dtype, torch)
     print(json.dumps(out), flush=True)

@@ -32,6 +32,12 @@
  *     or aborts across this boundary.  gac_strerror() names a code.
  *   - Results are deterministic: the same inputs, configuration and device give
  *     bit-identical sums, cosine and outputs on every call.
+ *   - Magnitudes: the three sums are accumulated in fp64, but each product g*d, g*g, d*d is
+ *     formed in fp32 first (exact for bf16 storage inside the fp32 exponent range).  Elements
+ *     with magnitude roughly in [1e-18, 1e18] are therefore safe; squares of smaller ones
+ *     underflow (a uniformly tiny gradient gives <g,g> = 0, c = 0, "safe") and squares of
+ *     larger ones overflow (GAC_ERR_NONFINITE).  c is scale invariant (Appendix A.1), so a
+ *     caller outside that range rescales g by a power of two.
  */
 #ifndef GAC_H_
 #define GAC_H_
@@ -57,8 +63,22 @@ enum {
   GAC_ERR_ALLOC = -3,          /* host or device allocation failed */
   GAC_ERR_HIP = -4,            /* a HIP runtime call failed; see gac_last_hip_error() */
   GAC_ERR_NONFINITE = -5,      /* a sum was inf/nan: nothing was modified (see gac_step) */
-  GAC_ERR_UNIMPLEMENTED = -6
+  GAC_ERR_UNIMPLEMENTED = -6   /* this combination of entry point and configuration is not built */
 };
+
+/* gac_config.flags */
+#define GAC_FLAG_SNAPSHOT_IN_REDUCE 1u
+/* Snapshot form, for callers that cannot swap buffers (gac_step_exchange) but whose steps are
+ * mostly safe (Table 3 of the paper: 83-99 % of on-policy steps have |c_t| <= 0.05).  The library
+ * keeps TWO state buffers; pass 1 writes the raw gradient into the spare one while it reduces
+ * (Appendix A.2: the gradient snapshot), and the finalize step makes that buffer the current
+ * reference state.  A step that neither projects nor clips then has no second pass: 3 N s
+ * bytes instead of 4 N s.  A projecting step reads g and the old state and rewrites g
+ * (3 N s + 3 N s, two mixed passes instead of one pure read pass and one mixed pass, so it
+ * is slower than the default form).  Results are bit-identical to the default form in every
+ * regime.  Costs N s bytes of device memory.  Needs a library-allocated state (state_ptrs =
+ * NULL); works with gac_step and gac_reduce_local / gac_apply; gac_step_adamw and
+ * gac_place_state return GAC_ERR_UNIMPLEMENTED on such a context. */
 
 typedef struct gac_config {
   double c_low;   /* Section 4.2; paper default 0.05 (Appendix C, "GAC thresholds") */
@@ -72,7 +92,7 @@ typedef struct gac_config {
                               numel[j] elements of dtype, or NULL: the library allocates
                               (and frees in gac_destroy) one buffer for all of d */
   int32_t device;          /* HIP device ordinal; -1 = current device */
-  uint32_t flags;          /* must be 0 */
+  uint32_t flags;          /* 0 or GAC_FLAG_SNAPSHOT_IN_REDUCE */
   int32_t chunk_elems;     /* tuning: elements per work item of a block; 0 = default.
                               Must be a positive multiple of 2048. */
   int32_t grid_blocks;     /* tuning: workgroups of the reduction launch (= number of partial
@@ -254,6 +274,9 @@ typedef struct gac_placement {
   double reduce_ms[GAC_MAX_PLACEMENT_CANDIDATES]; /* reduction pass time per location */
   int32_t blocks_tried[4];
   double blocks_ms[4];  /* probe time at the chosen location per workgroup count */
+  int64_t bytes_held_peak; /* most device memory the search held at one time beyond the state
+                              itself (candidates and spacers), in bytes; all of it is freed again
+                              except, after a move, what the old state occupied */
 } gac_placement;
 int gac_place_state(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidates,
                     int64_t max_extra_bytes, void* hip_stream, gac_placement* report);
@@ -296,7 +319,10 @@ int gac_plan_query(const int64_t* numel, int32_t n_tensors, int32_t dtype, int32
 /* Kernel timing for benchmarks.  While enabled, each step records HIP events on its stream
  * around the reduction, the finalize and the apply kernels.  gac_profile_read waits for the
  * recorded events and returns the summed milliseconds per kernel and the number of steps
- * since the last read (which it then clears).  At most 1024 steps are kept. */
+ * since the last read (which it then clears).  At most 1024 steps are kept.  The finalize
+ * step runs inside the reduction kernel (its last workgroup to finish), so ms_finalize is
+ * the empty interval between two events except for gac_apply, which has a finalize launch
+ * of its own.  The events cost a few microseconds per step: keep them out of timed runs. */
 int gac_profile_enable(gac_ctx* ctx, int32_t on);
 int gac_profile_read(gac_ctx* ctx, double* ms_reduce, double* ms_finalize, double* ms_apply,
                      int32_t* n_steps);
@@ -306,6 +332,9 @@ const char* gac_strerror(int code);
  * the last HIP error of any context on the calling thread (for a failed gac_init). */
 const char* gac_last_hip_error(const gac_ctx* ctx);
 const char* gac_version(void);
+/* SHA-256 (hex) of the sources this binary was built from, as the build recorded it ("" if it
+ * did not); lets a loader refuse a binary that does not belong to the sources beside it. */
+const char* gac_source_hash(void);
 
 #ifdef __cplusplus
 }

@@ -25,6 +25,8 @@ ERR_HIP = -4
 ERR_NONFINITE = -5
 ERR_UNIMPLEMENTED = -6
 
+FLAG_SNAPSHOT_IN_REDUCE = 1
+
 
 class GacConfig(ctypes.Structure):
     _fields_ = [("c_low", ctypes.c_double), ("c_high", ctypes.c_double), ("eps", ctypes.c_double),
@@ -63,7 +65,8 @@ class GacPlacement(ctypes.Structure):
                 ("apply_blocks", ctypes.c_int32), ("n_blocks_tried", ctypes.c_int32),
                 ("probe_ms", ctypes.c_double * MAX_PLACEMENT_CANDIDATES),
                 ("reduce_ms", ctypes.c_double * MAX_PLACEMENT_CANDIDATES),
-                ("blocks_tried", ctypes.c_int32 * 4), ("blocks_ms", ctypes.c_double * 4)]
+                ("blocks_tried", ctypes.c_int32 * 4), ("blocks_ms", ctypes.c_double * 4),
+                ("bytes_held_peak", ctypes.c_int64)]
 
 
 class GacAdamWHyper(ctypes.Structure):
@@ -83,8 +86,9 @@ _lib: Optional[ctypes.CDLL] = None
 
 
 def lib() -> ctypes.CDLL:
-    """Opens libgac.so.  It is built only if it does not exist at all; a stale or missing
-    library is never replaced by another code path."""
+    """Opens libgac.so.  It is built only if it does not exist at all.  A library that was built
+    from other sources than the ones beside it is refused (build again: python
+    __graft_entry__.py); a stale or missing library is never replaced by another code path."""
     global _lib
     if _lib is not None:
         return _lib
@@ -125,10 +129,16 @@ def lib() -> ctypes.CDLL:
         "gac_strerror": (ctypes.c_char_p, [ctypes.c_int]),
         "gac_last_hip_error": (ctypes.c_char_p, [vp]),
         "gac_version": (ctypes.c_char_p, []),
+        "gac_source_hash": (ctypes.c_char_p, []),
     }
     for name, (res, args) in sig.items():
         f = getattr(L, name)
         f.restype, f.argtypes = res, args
+    built_from = L.gac_source_hash().decode()
+    if built_from != _build.source_hash():
+        raise RuntimeError(
+            f"{_build.LIB_PATH} was built from other sources (hash {built_from[:12] or 'none'}, "
+            f"sources {_build.source_hash()[:12]}): build again with python __graft_entry__.py")
     _lib = L
     return L
 
@@ -169,27 +179,38 @@ def gac_plan_query(numel: Sequence[int], dtype: int, chunk_elems: int = 0):
     return nc.value, tot.value
 
 
+def make_config(numel: Sequence[int], dtype: int, c_low: float = 0.05, c_high: float = 0.3,
+                eps: float = 1e-8, beta: float = 1.0, state: Optional[Sequence] = None, device: int = -1,
+                chunk_elems: int = 0, grid_blocks: int = 0, apply_blocks: int = 0,
+                max_grad_norm: float = 0.0, history_capacity: int = 0, flags: int = 0):
+    """A filled gac_config and the ctypes arrays it points to (keep them alive with it)."""
+    cfg = GacConfig()
+    lib().gac_default_config(ctypes.byref(cfg))
+    cfg.c_low, cfg.c_high, cfg.eps, cfg.beta = c_low, c_high, eps, beta
+    cfg.dtype, cfg.n_tensors = dtype, len(numel)
+    numel_arr = (ctypes.c_int64 * len(numel))(*numel)
+    cfg.numel = numel_arr
+    state_ptrs = ptr_list(state)
+    if state_ptrs is not None:
+        cfg.state_ptrs = ctypes.cast(state_ptrs, ctypes.POINTER(ctypes.c_void_p))
+    cfg.device, cfg.chunk_elems, cfg.grid_blocks = device, chunk_elems, grid_blocks
+    cfg.apply_blocks = apply_blocks
+    cfg.max_grad_norm, cfg.history_capacity, cfg.flags = max_grad_norm, history_capacity, flags
+    return cfg, (numel_arr, state_ptrs)
+
+
 class Gac:
     """One GAC context (gac_init ... gac_destroy) over a fixed list of tensor sizes."""
 
     def __init__(self, numel: Sequence[int], dtype: int, c_low: float = 0.05, c_high: float = 0.3,
                  eps: float = 1e-8, beta: float = 1.0, state: Optional[Sequence] = None,
                  device: int = -1, chunk_elems: int = 0, grid_blocks: int = 0, apply_blocks: int = 0,
-                 max_grad_norm: float = 0.0, history_capacity: int = 0):
+                 max_grad_norm: float = 0.0, history_capacity: int = 0, flags: int = 0):
         L = lib()
-        cfg = GacConfig()
-        L.gac_default_config(ctypes.byref(cfg))
-        cfg.c_low, cfg.c_high, cfg.eps, cfg.beta = c_low, c_high, eps, beta
-        cfg.dtype, cfg.n_tensors = dtype, len(numel)
-        self._numel = (ctypes.c_int64 * len(numel))(*numel)
-        cfg.numel = self._numel
+        cfg, keep = make_config(numel, dtype, c_low, c_high, eps, beta, state, device, chunk_elems,
+                                grid_blocks, apply_blocks, max_grad_norm, history_capacity, flags)
+        self._numel, self._state_ptrs = keep
         self._state_keepalive = state
-        self._state_ptrs = ptr_list(state)
-        if self._state_ptrs is not None:
-            cfg.state_ptrs = ctypes.cast(self._state_ptrs, ctypes.POINTER(ctypes.c_void_p))
-        cfg.device, cfg.chunk_elems, cfg.grid_blocks = device, chunk_elems, grid_blocks
-        cfg.apply_blocks = apply_blocks
-        cfg.max_grad_norm, cfg.history_capacity = max_grad_norm, history_capacity
         self._ctx = ctypes.c_void_p()
         rc = L.gac_init(ctypes.byref(self._ctx), ctypes.byref(cfg))
         if rc != OK:

@@ -20,16 +20,22 @@ HIPCC_FLAGS = [
 ]
 
 
-def is_stale() -> bool:
-    if not os.path.exists(LIB_PATH):
-        return True
-    t = os.path.getmtime(LIB_PATH)
-    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
+def source_hash() -> str:
+    """SHA-256 over the bytes of every source and header the library is built from.  The build
+    compiles it into the library (gac_source_hash()), and the binding refuses a library whose
+    hash is not that of the sources next to it: a stale binary is an error, never a silent
+    stand-in."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in SOURCES + HEADERS:
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
 
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + SOURCES + ["-o", LIB_PATH]
+    cmd = [hipcc] + HIPCC_FLAGS + ['-DGAC_SOURCE_HASH="%s"' % source_hash()] + SOURCES + ["-o", LIB_PATH]
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, capture_output=True, text=True)

@@ -96,6 +96,14 @@ struct gac_ctx {
   void* state_alloc = nullptr; // owned allocation backing `state`, or null
   bool state_is_callers = false;  // the state buffers were provided by the caller
 
+  // Snapshot form (GAC_FLAG_SNAPSHOT_IN_REDUCE): a second state block with the same slicing,
+  // snap_delta bytes from the first; *dev_cur says which of the two is the reference state.
+  bool snapshot = false;
+  void* state1_alloc = nullptr;
+  std::vector<void*> state1;
+  int64_t snap_delta = 0;
+  int32_t* dev_cur = nullptr;
+
   // pointer tables
   Seg* dev_segs = nullptr;        // (gradient, state) per tensor: the table the step kernels read
   Seg* dev_segs_state = nullptr;  // (source, destination) of state copies / zeroing: kept apart so
@@ -113,6 +121,7 @@ struct gac_ctx {
   bool adam_valid = false;
 
   double* dev_partials = nullptr;  // 3 doubles per workgroup
+  unsigned int* dev_ticket = nullptr;  // arrival counter of the reduction's workgroups (zero between launches)
   double* dev_sums = nullptr;      // 3 doubles
   gac_result* dev_result = nullptr;
   gac_result* pinned_result = nullptr;      // host address of the pinned result record
@@ -242,8 +251,10 @@ int check_ptrs(const gac_ctx* ctx, const void* const* ptrs) {
 // In place the gradient and the reference state are read and written by the same pass, so a
 // gradient buffer that IS the state buffer cannot work; partial overlaps are the caller's to avoid.
 int check_not_state(const gac_ctx* ctx, void* const* grad_ptrs) {
-  for (int j = 0; j < ctx->n_tensors; ++j)
+  for (int j = 0; j < ctx->n_tensors; ++j) {
     if (ctx->numel[j] > 0 && grad_ptrs[j] == ctx->state[j]) return GAC_ERR_INVALID_ARG;
+    if (ctx->snapshot && ctx->numel[j] > 0 && grad_ptrs[j] == ctx->state1[j]) return GAC_ERR_INVALID_ARG;
+  }
   return GAC_OK;
 }
 
@@ -315,6 +326,8 @@ DecideParams decide_params(const gac_ctx* ctx) {
   p.hist_c = ctx->hist_c;
   p.hist_regime = ctx->hist_regime;
   p.hist_cap = ctx->hist_cap;
+  p.step_value = 0;
+  p.cur = ctx->snapshot ? ctx->dev_cur : nullptr;
   return p;
 }
 
@@ -326,7 +339,7 @@ int state_op(gac_ctx* ctx, int op, const void* const* src, void* const* dst, hip
   return GAC_OK;
 }
 
-// Steps shared by gac_step / gac_apply / gac_step_adamw after the sums are available.
+// Steps shared by gac_step / gac_apply / gac_step_adamw / gac_step_exchange.
 enum class ApplyKind { kPlain, kAdamW, kExchange };
 
 int run_step(gac_ctx* ctx, void* const* grad_ptrs, bool do_reduce, const double* sums_in,
@@ -335,16 +348,19 @@ int run_step(gac_ctx* ctx, void* const* grad_ptrs, bool do_reduce, const double*
   if (rc != GAC_OK) return rc;
   StepEvents* ev = next_events(ctx);
   if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[0], stream));
-  int mode = 2;
+  gac_result* host_res = host_out ? ctx->pinned_result_dev : nullptr;
   if (do_reduce) {
+    // the last workgroup of the reduction to finish also decides the regime
     GAC_HIP(ctx, gac::launch_reduce(ctx->dtype, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
-                                    ctx->dev_partials, ctx->grid, stream));
-    mode |= 1;
+                                    ctx->dev_partials, ctx->dev_ticket, ctx->grid, ctx->dev_sums,
+                                    ctx->dev_result, host_res, decide_params(ctx), /*mode=*/2,
+                                    ctx->snap_delta, stream));
+    if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[1], stream));
+  } else {
+    if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[1], stream));
+    GAC_HIP(ctx, gac::launch_finalize(sums_in, ctx->dev_sums, ctx->dev_result, host_res,
+                                      decide_params(ctx), stream));
   }
-  if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[1], stream));
-  GAC_HIP(ctx, gac::launch_finalize(ctx->dev_partials, ctx->grid, sums_in, ctx->dev_sums,
-                                    ctx->dev_result, host_out ? ctx->pinned_result_dev : nullptr,
-                                    decide_params(ctx), mode, stream));
   if (host_out != nullptr) {
     rc = mark_result(ctx, stream);
     if (rc != GAC_OK) return rc;
@@ -353,6 +369,10 @@ int run_step(gac_ctx* ctx, void* const* grad_ptrs, bool do_reduce, const double*
   if (kind == ApplyKind::kExchange) {
     GAC_HIP(ctx, gac::launch_exchange(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
                                       ctx->chunk_elems, ctx->dev_result, ctx->grid_apply, stream));
+  } else if (kind == ApplyKind::kPlain && ctx->snapshot) {
+    GAC_HIP(ctx, gac::launch_snap_apply(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
+                                        ctx->chunk_elems, ctx->dev_result, ctx->dev_cur,
+                                        ctx->snap_delta, ctx->grid_apply, stream));
   } else if (kind == ApplyKind::kPlain) {
     GAC_HIP(ctx, gac::launch_apply(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
                                    ctx->chunk_elems, ctx->dev_result, ctx->grid_apply, stream));
@@ -363,6 +383,15 @@ int run_step(gac_ctx* ctx, void* const* grad_ptrs, bool do_reduce, const double*
   }
   if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[3], stream));
   if (host_out != nullptr) return wait_result(ctx, host_out);
+  return GAC_OK;
+}
+
+// Which of the two state buffers of the snapshot form is current (waits for the stream).
+int read_cur(gac_ctx* ctx, hipStream_t stream, int32_t* out) {
+  *out = 0;
+  if (!ctx->snapshot) return GAC_OK;
+  GAC_HIP(ctx, hipStreamSynchronize(stream));
+  GAC_HIP(ctx, hipMemcpy(out, ctx->dev_cur, sizeof(int32_t), hipMemcpyDeviceToHost));
   return GAC_OK;
 }
 
@@ -414,7 +443,7 @@ int gac_init(gac_ctx** out, const gac_config* cfg) {
 namespace {
 int init_impl(gac_ctx** out, const gac_config* cfg) {
   if (cfg == nullptr || cfg->n_tensors < 0 || (cfg->n_tensors > 0 && cfg->numel == nullptr) ||
-      cfg->flags != 0 || cfg->grid_blocks < 0 || cfg->grid_blocks > gac::kMaxGridBlocks ||
+      (cfg->flags & ~GAC_FLAG_SNAPSHOT_IN_REDUCE) != 0 || cfg->grid_blocks < 0 || cfg->grid_blocks > gac::kMaxGridBlocks ||
       cfg->apply_blocks < 0 || cfg->apply_blocks > gac::kMaxGridBlocks || cfg->reserved != 0 ||
       cfg->history_capacity < 0 || cfg->history_capacity > gac::kMaxHistory)
     return GAC_ERR_INVALID_ARG;
@@ -450,6 +479,8 @@ int init_impl(gac_ctx** out, const gac_config* cfg) {
     for (int j = 0; j < n; ++j)
       if (ctx->numel[j] > 0 && cfg->state_ptrs[j] == nullptr) return GAC_ERR_INVALID_ARG;
   }
+  ctx->snapshot = (cfg->flags & GAC_FLAG_SNAPSHOT_IN_REDUCE) != 0;
+  if (ctx->snapshot && cfg->state_ptrs != nullptr) return GAC_ERR_INVALID_ARG;  // needs two buffers of its own
 
   // ---- from here on the GPU is touched
   int dev = cfg->device;
@@ -483,6 +514,11 @@ int init_impl(gac_ctx** out, const gac_config* cfg) {
   } else {
     rc = alloc_state_block(ctx, &ctx->state_alloc, &ctx->state);
     if (rc != GAC_OK) return rc;
+    if (ctx->snapshot) {
+      rc = alloc_state_block(ctx, &ctx->state1_alloc, &ctx->state1);
+      if (rc != GAC_OK) return rc;
+      ctx->snap_delta = static_cast<char*>(ctx->state1_alloc) - static_cast<char*>(ctx->state_alloc);
+    }
   }
   rc = check_ptrs(ctx, const_cast<const void* const*>(ctx->state.data()));
   if (rc != GAC_OK) return rc;
@@ -499,6 +535,10 @@ int init_impl(gac_ctx** out, const gac_config* cfg) {
   ctx->cached_b.assign(n, nullptr);
   ctx->cached_adam.assign(n, AdamSeg{nullptr, nullptr, nullptr, nullptr});
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_partials), sizeof(double) * 3 * ctx->grid));
+  GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_ticket), sizeof(unsigned int)));
+  GAC_HIP(ctx, gac::launch_set_word(ctx->dev_ticket, 0u, nullptr));
+  GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_cur), sizeof(int32_t)));
+  GAC_HIP(ctx, gac::launch_set_word(reinterpret_cast<uint32_t*>(ctx->dev_cur), 0u, nullptr));
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_sums), sizeof(double) * 3));
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_result), sizeof(gac_result)));
   GAC_HIP(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned_result), sizeof(gac_result),
@@ -521,6 +561,10 @@ int init_impl(gac_ctx** out, const gac_config* cfg) {
   // Algorithm 1: the reference state starts at zero.
   rc = state_op(ctx, gac::kStateZero, nullptr, ctx->state.data(), nullptr);
   if (rc != GAC_OK) return rc;
+  if (ctx->snapshot) {  // the spare buffer is written before it is read; zeroed for tidiness
+    rc = state_op(ctx, gac::kStateZero, nullptr, ctx->state1.data(), nullptr);
+    if (rc != GAC_OK) return rc;
+  }
   GAC_HIP(ctx, hipStreamSynchronize(nullptr));
 
   cleanup.c = nullptr;
@@ -535,6 +579,9 @@ void gac_destroy(gac_ctx* ctx) {
     DeviceGuard guard(ctx->device);
     (void)hipDeviceSynchronize();
     if (ctx->state_alloc) (void)hipFree(ctx->state_alloc);
+    if (ctx->state1_alloc) (void)hipFree(ctx->state1_alloc);
+    if (ctx->dev_ticket) (void)hipFree(ctx->dev_ticket);
+    if (ctx->dev_cur) (void)hipFree(ctx->dev_cur);
     if (ctx->dev_segs) (void)hipFree(ctx->dev_segs);
     if (ctx->dev_segs_state) (void)hipFree(ctx->dev_segs_state);
     if (ctx->dev_adam) (void)hipFree(ctx->dev_adam);
@@ -595,10 +642,11 @@ int gac_reduce_local(gac_ctx* ctx, void* const* grad_ptrs, void* hip_stream, dou
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   rc = upload_segs(ctx, const_cast<const void* const*>(grad_ptrs), ctx->state.data(), stream);
   if (rc != GAC_OK) return rc;
+  // sums only: the regime is decided in phase 2, on the global sums
   GAC_HIP(ctx, gac::launch_reduce(ctx->dtype, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
-                                  ctx->dev_partials, ctx->grid, stream));
-  GAC_HIP(ctx, gac::launch_finalize(ctx->dev_partials, ctx->grid, nullptr, dev_sums3, ctx->dev_result,
-                                    nullptr, decide_params(ctx), /*mode=*/1, stream));  // sums only
+                                  ctx->dev_partials, ctx->dev_ticket, ctx->grid, dev_sums3,
+                                  ctx->dev_result, nullptr, decide_params(ctx), /*mode=*/0,
+                                  ctx->snap_delta, stream));
   return GAC_OK;
 }
 
@@ -617,6 +665,7 @@ int gac_step_adamw(gac_ctx* ctx, void* const* grad_ptrs, float* const* master_p,
                    float* const* v, void* const* p_lowp, const gac_adamw_hyper* hyper,
                    void* hip_stream, gac_result* host_out) {
   if (ctx == nullptr || hyper == nullptr) return GAC_ERR_INVALID_ARG;
+  if (ctx->snapshot) return GAC_ERR_UNIMPLEMENTED;
   int rc = check_ptrs(ctx, const_cast<const void* const*>(grad_ptrs));
   if (rc == GAC_OK) rc = check_not_state(ctx, grad_ptrs);
   if (rc != GAC_OK) return rc;
@@ -668,7 +717,11 @@ int gac_state_export(gac_ctx* ctx, void* const* dst_ptrs, int64_t* step_out, voi
     rc = read_step(ctx, static_cast<hipStream_t>(hip_stream), step_out);
     if (rc != GAC_OK) return rc;
   }
-  return state_op(ctx, gac::kStateCopy, const_cast<const void* const*>(ctx->state.data()), dst_ptrs,
+  int32_t cur = 0;
+  rc = read_cur(ctx, static_cast<hipStream_t>(hip_stream), &cur);
+  if (rc != GAC_OK) return rc;
+  const std::vector<void*>& src = cur ? ctx->state1 : ctx->state;
+  return state_op(ctx, gac::kStateCopy, const_cast<const void* const*>(src.data()), dst_ptrs,
                   static_cast<hipStream_t>(hip_stream));
 }
 
@@ -681,6 +734,9 @@ int gac_state_import(gac_ctx* ctx, void* const* src_ptrs, int64_t step, void* hi
                 static_cast<hipStream_t>(hip_stream));
   if (rc == GAC_OK) {
     GAC_HIP(ctx, gac::launch_set_step(ctx->dev_step, step, static_cast<hipStream_t>(hip_stream)));
+    // snapshot form: the imported state went into buffer 0, which becomes the current one
+    GAC_HIP(ctx, gac::launch_set_word(reinterpret_cast<uint32_t*>(ctx->dev_cur), 0u,
+                                      static_cast<hipStream_t>(hip_stream)));
     ctx->hist_first = step + 1;
   }
   return rc;
@@ -692,6 +748,8 @@ int gac_reset(gac_ctx* ctx, void* hip_stream) {
   int rc = state_op(ctx, gac::kStateZero, nullptr, ctx->state.data(), static_cast<hipStream_t>(hip_stream));
   if (rc == GAC_OK) {
     GAC_HIP(ctx, gac::launch_set_step(ctx->dev_step, 0, static_cast<hipStream_t>(hip_stream)));
+    GAC_HIP(ctx, gac::launch_set_word(reinterpret_cast<uint32_t*>(ctx->dev_cur), 0u,
+                                      static_cast<hipStream_t>(hip_stream)));
     ctx->hist_first = 1;
   }
   return rc;
@@ -708,8 +766,11 @@ int time_probe(gac_ctx* ctx, void* const* grad_ptrs, void* const* state_ptrs, bo
   for (int i = -1; i < 3; ++i) {
     GAC_HIP(ctx, hipEventRecord(e0, stream));
     if (reduce) {
+      // sums only (mode 0): no step is counted and no result is written
       GAC_HIP(ctx, gac::launch_reduce(ctx->dtype, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
-                                      ctx->dev_partials, ctx->grid, stream));
+                                      ctx->dev_partials, ctx->dev_ticket, ctx->grid, ctx->dev_sums,
+                                      ctx->dev_result, nullptr, decide_params(ctx), /*mode=*/0,
+                                      0, stream));
     } else {
       GAC_HIP(ctx, gac::launch_apply_probe(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
                                            ctx->chunk_elems, grid, stream));
@@ -830,6 +891,7 @@ int place_state_impl(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidate
       ++since_best;
     }
   }
+  rep->bytes_held_peak = extra;  // nothing is released before the end of the search
   if (rc != GAC_OK) return fail(rc);
   rep->n_candidates = static_cast<int>(cand.size());
   auto both = [&](int c) { return rep->probe_ms[c] + rep->reduce_ms[c]; };
@@ -895,6 +957,7 @@ int gac_place_state(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidates
   if (ctx == nullptr || max_candidates < 1 || max_candidates > GAC_MAX_PLACEMENT_CANDIDATES ||
       max_extra_bytes < 0 || (ctx->state_is_callers && max_candidates != 1))
     return GAC_ERR_INVALID_ARG;
+  if (ctx->snapshot) return GAC_ERR_UNIMPLEMENTED;
   int rc = check_ptrs(ctx, const_cast<const void* const*>(grad_ptrs));
   if (rc == GAC_OK) rc = check_not_state(ctx, grad_ptrs);
   if (rc != GAC_OK) return rc;
@@ -1051,7 +1114,7 @@ const char* gac_strerror(int code) {
     case GAC_ERR_ALLOC: return "allocation failed";
     case GAC_ERR_HIP: return "HIP runtime error";
     case GAC_ERR_NONFINITE: return "non-finite gradient statistics; nothing was modified";
-    case GAC_ERR_UNIMPLEMENTED: return "not implemented";
+    case GAC_ERR_UNIMPLEMENTED: return "not implemented for this configuration";
     default: return "unknown error code";
   }
 }
@@ -1060,6 +1123,11 @@ const char* gac_last_hip_error(const gac_ctx* ctx) {
   return ctx ? ctx->hip_err.c_str() : g_last_hip_error.c_str();
 }
 
-const char* gac_version(void) { return "gac-mi355x 0.1"; }
+const char* gac_version(void) { return "gac-mi355x 0.2"; }
+
+#ifndef GAC_SOURCE_HASH
+#define GAC_SOURCE_HASH ""
+#endif
+const char* gac_source_hash(void) { return GAC_SOURCE_HASH; }
 
 }  // extern "C"

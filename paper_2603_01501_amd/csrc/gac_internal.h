@@ -38,6 +38,9 @@ struct DecideParams {
   double* hist_c;        // ring of recorded cosines, hist_cap entries (or null)
   int32_t* hist_regime;  // ring of recorded regimes
   int32_t hist_cap;
+  int64_t step_value;    // used when `step` is null: the number this update gets (the caller counts)
+  int32_t* cur;          // snapshot form: which of the two state buffers is current (flipped by a
+                         // finite step); null otherwise
 };
 
 constexpr int kMaxHistory = 4096;  // the statistics kernel sorts the ring in LDS
@@ -63,14 +66,20 @@ int adamw_blocks_per_cu(int dtype);
 
 // Launchers (defined in gac_kernels.hip).  Each validates nothing: the host side has
 // already checked shapes against the plan.  All return the launch's hipError_t.
+// Pass 1 with the finalize step folded into its last-arriving workgroup.  The sums go to
+// sums_out (if not null).  mode bit 1: decide and write the result record to dev_result and,
+// if not null, also to host_result (host-mapped pinned memory).  dev_ticket is one zero
+// word that the kernel leaves at zero.  With p.cur set (snapshot form) the raw gradient is
+// also written to the state buffer that is not current, snap_delta bytes from the other.
 hipError_t launch_reduce(int dtype, const Seg* dev_segs, int64_t n_chunks, int chunk_elems,
-                         double* dev_partials, int grid, hipStream_t stream);
+                         double* dev_partials, unsigned int* dev_ticket, int grid, double* sums_out,
+                         gac_result* dev_result, gac_result* host_result, DecideParams p, int mode,
+                         int64_t snap_delta, hipStream_t stream);
 
-// mode bit 0: combine partials into sums (else read sums_in); bit 1: decide and write result
-// to dev_result and, if not null, also to host_result (host-mapped pinned memory).
-hipError_t launch_finalize(const double* dev_partials, int n_partials, const double* sums_in,
-                           double* sums_out, gac_result* dev_result, gac_result* host_result,
-                           DecideParams p, int mode, hipStream_t stream);
+// The finalize step alone, on sums that come from elsewhere (device, 3 doubles): decides and
+// writes the result record like the folded form.
+hipError_t launch_finalize(const double* sums_in, double* sums_out, gac_result* dev_result,
+                           gac_result* host_result, DecideParams p, hipStream_t stream);
 
 hipError_t launch_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
                         int chunk_elems, const gac_result* dev_result, int grid, hipStream_t stream);
@@ -86,6 +95,12 @@ hipError_t launch_exchange(int dtype, const Seg* dev_segs, int n_tensors, int64_
                            int chunk_elems, const gac_result* dev_result, int grid,
                            hipStream_t stream);
 
+// Pass 2 of the snapshot form: g <- scale_g g + coef_d d_old in place when the step projects or
+// clips, nothing otherwise (the state was already written by pass 1).
+hipError_t launch_snap_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
+                             int chunk_elems, const gac_result* dev_result, int32_t* dev_cur,
+                             int64_t snap_delta, int grid, hipStream_t stream);
+
 // The same traffic as the projecting apply pass with every value written back unchanged.
 hipError_t launch_apply_probe(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
                               int chunk_elems, int grid, hipStream_t stream);
@@ -94,8 +109,6 @@ hipError_t launch_apply_adamw(int dtype, const Seg* dev_segs, const AdamSeg* dev
                               const gac_result* dev_result, AdamScalars h, int grid,
                               hipStream_t stream);
 
-// Sets the device-side step counter (init / reset / import); a one-thread kernel rather than
-// a memset so that it can sit in a captured graph.
 // Threshold pairs of one sweep, passed to the kernel by value.
 struct SweepPairs {
   double c_low[64];
@@ -104,7 +117,11 @@ struct SweepPairs {
 hipError_t launch_sweep(const double* hist_c, const int32_t* hist_regime, int hist_cap,
                         int64_t first_step, int64_t last_step, const SweepPairs& pairs,
                         int n_pairs, int32_t* host_counts, hipStream_t stream);
+// Set the device-side step counter (init / reset / import) or one 32-bit word (ticket counter,
+// current-buffer flag); one-thread kernels rather than memsets so that they can sit in a
+// captured graph.
 hipError_t launch_set_step(int64_t* dev_step, int64_t value, hipStream_t stream);
+hipError_t launch_set_word(uint32_t* dev_word, uint32_t value, hipStream_t stream);
 
 hipError_t launch_state_op(int dtype, int op, const Seg* dev_segs, int64_t n_chunks,
                            int chunk_elems, int grid, hipStream_t stream);

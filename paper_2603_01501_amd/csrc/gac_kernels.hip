@@ -240,123 +240,35 @@ __device__ __forceinline__ void block_sum3(double (&s)[3]) {
   }
 }
 
-// ------------------------------------------------------------------ pass 1: reduction
-
-template <int DT>
-__device__ __forceinline__ void dot3(u32x4 a, u32x4 b, float& gd, float& gg, float& dd) {
-  constexpr int N = Elem<DT>::kPerVec;
-  float x[N], y[N];
-  unpack<DT>(a, x);
-  unpack<DT>(b, y);
-#pragma unroll
-  for (int e = 0; e < N; ++e) {
-    gd = fmaf(x[e], y[e], gd);
-    gg = fmaf(x[e], x[e], gg);
-    dd = fmaf(y[e], y[e], dd);
-  }
-}
-
-template <int DT, int T, int U>
-__global__ __launch_bounds__(T) void reduce_kernel(const Seg* __restrict__ segs,
-                                                          int64_t n_chunks, int chunk_elems,
-                                                          double* __restrict__ partials) {
-  constexpr int N = Elem<DT>::kPerVec;
-  const int tid = threadIdx.x;
-  double acc[3] = {0.0, 0.0, 0.0};
-  int t = 0;
-  int64_t c = blockIdx.x;
-  bool more = c < n_chunks;
-  Chunk next = {};
-  if (more) next = locate<false>(segs, t, c, chunk_elems, Elem<DT>::kSize);
-  while (more) {
-    const Chunk ch = next;
-    // Look up the following chunk now: its dependent scalar loads from the tensor table
-    // then overlap this chunk's streaming instead of stalling the workgroup between chunks.
-    c += gridDim.x;
-    more = c < n_chunks;
-    if (more) next = locate<false>(segs, t, c, chunk_elems, Elem<DT>::kSize);
-    {
-      const gvec* __restrict__ gv = reinterpret_cast<const gvec*>(ch.a);
-      const gvec* __restrict__ dv = reinterpret_cast<const gvec*>(ch.b);
-      const int nvec = ch.len / N;
-      int i = tid;
-      for (; i + (U - 1) * T < nvec; i += U * T) {
-        u32x4 a[U], b[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) a[u] = ld16<GAC_REDUCE_NT_LOAD>(gv + i + u * T);
-#pragma unroll
-        for (int u = 0; u < U; ++u) b[u] = ld16<GAC_REDUCE_NT_LOAD>(dv + i + u * T);
-        float gd = 0.f, gg = 0.f, dd = 0.f;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          float pgd = 0.f, pgg = 0.f, pdd = 0.f;
-          dot3<DT>(a[u], b[u], pgd, pgg, pdd);
-          gd += pgd;
-          gg += pgg;
-          dd += pdd;
-        }
-        acc[0] += static_cast<double>(gd);
-        acc[1] += static_cast<double>(gg);
-        acc[2] += static_cast<double>(dd);
-      }
-      for (; i < nvec; i += T) {
-        float gd = 0.f, gg = 0.f, dd = 0.f;
-        dot3<DT>(ld16<GAC_REDUCE_NT_LOAD>(gv + i), ld16<GAC_REDUCE_NT_LOAD>(dv + i), gd, gg, dd);
-        acc[0] += static_cast<double>(gd);
-        acc[1] += static_cast<double>(gg);
-        acc[2] += static_cast<double>(dd);
-      }
-      const int e = nvec * N + tid;  // at most N-1 leftover elements
-      if (e < ch.len) {
-        const float x = load_elem<DT>(ch.a, e), y = load_elem<DT>(ch.b, e);
-        acc[0] += static_cast<double>(x * y);
-        acc[1] += static_cast<double>(x * x);
-        acc[2] += static_cast<double>(y * y);
-      }
-    }
-  }
-  block_sum3<T>(acc);
-  if (tid == 0) {
-    partials[3 * blockIdx.x + 0] = acc[0];
-    partials[3 * blockIdx.x + 1] = acc[1];
-    partials[3 * blockIdx.x + 2] = acc[2];
-  }
-}
-
 // ------------------------------------------------------------------ finalize
 
-// mode bit 0: add the per-workgroup partials (fixed order) instead of reading sums_in;
-// mode bit 1: evaluate the cosine and the regime and write the result record.
-__global__ __launch_bounds__(kThreads) void finalize_kernel(const double* __restrict__ partials,
-                                                            int n_partials,
-                                                            const double* __restrict__ sums_in,
-                                                            double* __restrict__ sums_out,
-                                                            gac_result* __restrict__ res,
-                                                            gac_result* __restrict__ host_res,
-                                                            DecideParams p, int mode) {
-  double s[3] = {0.0, 0.0, 0.0};
-  if (mode & 1) {
-    for (int j = threadIdx.x; j < n_partials; j += kThreads) {
-      s[0] += partials[3 * j + 0];
-      s[1] += partials[3 * j + 1];
-      s[2] += partials[3 * j + 2];
-    }
-    block_sum3<kThreads>(s);
-  } else if (threadIdx.x == 0) {
-    s[0] = sums_in[0];
-    s[1] = sums_in[1];
-    s[2] = sums_in[2];
+// Adds the per-workgroup partial sums in a fixed order: lane j takes partials j, j+T, ...,
+// then a fixed tree over lanes and waves.  The result is valid in thread 0.
+template <int T>
+__device__ __forceinline__ void combine_partials(const double* __restrict__ partials, int n_partials,
+                                                 double (&s)[3]) {
+  s[0] = s[1] = s[2] = 0.0;
+  for (int j = threadIdx.x; j < n_partials; j += T) {
+    s[0] += partials[3 * j + 0];
+    s[1] += partials[3 * j + 1];
+    s[2] += partials[3 * j + 2];
   }
-  if (threadIdx.x != 0) return;
-  if (sums_out != nullptr) {
-    sums_out[0] = s[0];
-    sums_out[1] = s[1];
-    sums_out[2] = s[2];
-  }
-  if (!(mode & 2)) return;
+  block_sum3<T>(s);
+}
+
+// One thread: cosine with eps, regime, alpha, coefficients, clipping, the record of c_t and
+// the result (Appendix A.1, Section 4.2, Algorithm 1, Appendix A.2).
+__device__ __forceinline__ void decide_and_record(const double (&s)[3], const DecideParams& p,
+                                                  gac_result* __restrict__ res,
+                                                  gac_result* __restrict__ host_res) {
   const double s_gd = s[0], s_gg = s[1], s_dd = s[2];
-  const int64_t step = *p.step + 1;  // only this thread of this one-workgroup kernel touches it
-  *p.step = step;
+  int64_t step;
+  if (p.step != nullptr) {
+    step = *p.step + 1;  // only this one thread of the launch touches the counter
+    *p.step = step;
+  } else {
+    step = p.step_value;
+  }
   gac_result r;
   r.dot = s_gd;
   r.gg = s_gg;
@@ -413,10 +325,176 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const double* __rest
     p.hist_c[slot] = r.c;
     p.hist_regime[slot] = r.nonfinite ? -1 : r.regime;
   }
+  // The snapshot form keeps two state buffers; a finite step makes the one that pass 1 has
+  // just filled with the raw gradient the current one.
+  if (p.cur != nullptr && !r.nonfinite) *p.cur ^= 1;
   *res = r;
   // Optional second copy straight into host-mapped pinned memory: the host then learns the
   // regime by waiting on an event after this kernel, with no copy command in the stream.
   if (host_res != nullptr) *host_res = r;
+}
+
+// What follows the sums, for the kernel that has them.
+//   mode bit 0: the sums come from the per-workgroup partials (else from sums_in);
+//   mode bit 1: evaluate the cosine and the regime and write the result record.
+struct FinalArgs {
+  const double* sums_in;
+  double* sums_out;      // may be null
+  gac_result* res;
+  gac_result* host_res;  // may be null
+  DecideParams p;
+  int mode;
+};
+
+// Thread 0 holds the sums.
+__device__ __forceinline__ void finish(const double (&s)[3], const FinalArgs& f) {
+  if (f.sums_out != nullptr) {
+    f.sums_out[0] = s[0];
+    f.sums_out[1] = s[1];
+    f.sums_out[2] = s[2];
+  }
+  if (f.mode & 2) decide_and_record(s, f.p, f.res, f.host_res);
+}
+
+// Stand-alone form, for sums that come from elsewhere (the data-parallel phase 2).
+__global__ __launch_bounds__(kThreads) void finalize_kernel(const double* __restrict__ partials,
+                                                            int n_partials, FinalArgs f) {
+  double s[3] = {0.0, 0.0, 0.0};
+  if (f.mode & 1) {
+    combine_partials<kThreads>(partials, n_partials, s);
+  } else if (threadIdx.x == 0) {
+    s[0] = f.sums_in[0];
+    s[1] = f.sums_in[1];
+    s[2] = f.sums_in[2];
+  }
+  if (threadIdx.x == 0) finish(s, f);
+}
+
+// ------------------------------------------------------------------ pass 1: reduction
+
+template <int DT>
+__device__ __forceinline__ void dot3(u32x4 a, u32x4 b, float& gd, float& gg, float& dd) {
+  constexpr int N = Elem<DT>::kPerVec;
+  float x[N], y[N];
+  unpack<DT>(a, x);
+  unpack<DT>(b, y);
+#pragma unroll
+  for (int e = 0; e < N; ++e) {
+    gd = fmaf(x[e], y[e], gd);
+    gg = fmaf(x[e], x[e], gg);
+    dd = fmaf(y[e], y[e], dd);
+  }
+}
+
+// The snapshot form keeps two buffers per state tensor, `delta` bytes apart (Seg::b is buffer
+// 0); *cur says which one holds the reference state.  Pass 1 then also writes the raw gradient
+// into the other one, which the finalize step makes current, so that a step that neither
+// projects nor clips needs no second pass at all (3 N s bytes instead of 4 N s).
+struct SnapArgs {
+  int32_t* cur;
+  int64_t delta;
+};
+
+// Pass 1.  Besides its partial sums every workgroup takes a ticket (an integer atomic, so the
+// order of arrival changes nothing in the result); the one that draws the last ticket knows
+// that all partial sums have been written, adds them in the fixed order and does what follows
+// the sums (FinalArgs), so the step needs no separate finalize launch.  It also puts the
+// ticket counter back to zero for the next launch.
+template <int DT, int T, int U, bool SNAP>
+__global__ __launch_bounds__(T) void reduce_kernel(const Seg* __restrict__ segs,
+                                                          int64_t n_chunks, int chunk_elems,
+                                                          double* __restrict__ partials,
+                                                          unsigned int* __restrict__ ticket,
+                                                          FinalArgs fin, SnapArgs snap) {
+  constexpr int N = Elem<DT>::kPerVec;
+  const int tid = threadIdx.x;
+  int64_t d_off = 0, spare_off = 0;  // byte offsets from Seg::b of the state read / the buffer written
+  if constexpr (SNAP) {
+    if (*snap.cur) {
+      d_off = snap.delta;
+    } else {
+      spare_off = snap.delta;
+    }
+  }
+  double acc[3] = {0.0, 0.0, 0.0};
+  int t = 0;
+  int64_t c = blockIdx.x;
+  bool more = c < n_chunks;
+  Chunk next = {};
+  if (more) next = locate<false>(segs, t, c, chunk_elems, Elem<DT>::kSize);
+  while (more) {
+    const Chunk ch = next;
+    // Look up the following chunk now: its dependent scalar loads from the tensor table
+    // then overlap this chunk's streaming instead of stalling the workgroup between chunks.
+    c += gridDim.x;
+    more = c < n_chunks;
+    if (more) next = locate<false>(segs, t, c, chunk_elems, Elem<DT>::kSize);
+    {
+      const gvec* __restrict__ gv = reinterpret_cast<const gvec*>(ch.a);
+      const gvec* __restrict__ dv = reinterpret_cast<const gvec*>(ch.b + d_off);
+      gvec* __restrict__ sv = reinterpret_cast<gvec*>(ch.b + spare_off);
+      const int nvec = ch.len / N;
+      int i = tid;
+      for (; i + (U - 1) * T < nvec; i += U * T) {
+        u32x4 a[U], b[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) a[u] = ld16<GAC_REDUCE_NT_LOAD>(gv + i + u * T);
+#pragma unroll
+        for (int u = 0; u < U; ++u) b[u] = ld16<GAC_REDUCE_NT_LOAD>(dv + i + u * T);
+        if constexpr (SNAP) {
+#pragma unroll
+          for (int u = 0; u < U; ++u) st16<1>(sv + i + u * T, a[u]);
+        }
+        float gd = 0.f, gg = 0.f, dd = 0.f;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          float pgd = 0.f, pgg = 0.f, pdd = 0.f;
+          dot3<DT>(a[u], b[u], pgd, pgg, pdd);
+          gd += pgd;
+          gg += pgg;
+          dd += pdd;
+        }
+        acc[0] += static_cast<double>(gd);
+        acc[1] += static_cast<double>(gg);
+        acc[2] += static_cast<double>(dd);
+      }
+      for (; i < nvec; i += T) {
+        float gd = 0.f, gg = 0.f, dd = 0.f;
+        const u32x4 a = ld16<GAC_REDUCE_NT_LOAD>(gv + i);
+        dot3<DT>(a, ld16<GAC_REDUCE_NT_LOAD>(dv + i), gd, gg, dd);
+        if constexpr (SNAP) st16<1>(sv + i, a);
+        acc[0] += static_cast<double>(gd);
+        acc[1] += static_cast<double>(gg);
+        acc[2] += static_cast<double>(dd);
+      }
+      const int e = nvec * N + tid;  // at most N-1 leftover elements
+      if (e < ch.len) {
+        const float x = load_elem<DT>(ch.a, e), y = load_elem<DT>(ch.b + d_off, e);
+        if constexpr (SNAP) copy_elem<DT>(ch.a, ch.b + spare_off, e);
+        acc[0] += static_cast<double>(x * y);
+        acc[1] += static_cast<double>(x * x);
+        acc[2] += static_cast<double>(y * y);
+      }
+    }
+  }
+  block_sum3<T>(acc);
+  __shared__ int last_arrival;
+  if (tid == 0) {
+    partials[3 * blockIdx.x + 0] = acc[0];
+    partials[3 * blockIdx.x + 1] = acc[1];
+    partials[3 * blockIdx.x + 2] = acc[2];
+    __threadfence();  // the partial sums are visible device-wide before the ticket is drawn
+    last_arrival = atomicAdd(ticket, 1u) == gridDim.x - 1;
+  }
+  __syncthreads();
+  if (!last_arrival) return;
+  __threadfence();  // every other workgroup's partial sums are read from memory, not from a stale cache line
+  double s[3];
+  combine_partials<T>(partials, static_cast<int>(gridDim.x), s);
+  if (tid == 0) {
+    finish(s, fin);
+    *ticket = 0u;
+  }
 }
 
 // ------------------------------------------------------------------ pass 2: apply
@@ -614,6 +692,53 @@ __global__ __launch_bounds__(T) void exchange_kernel(const Seg* __restrict__ seg
                                                        ld16<GAC_APPLY_NT_LOAD>(dv + i), k, beta));
     for (int i = nvec * N + tid; i < ch.len; i += T)
       store_elem<DT>(ch.b, i, fmaf(k, load_elem<DT>(ch.b, i), beta * load_elem<DT>(ch.a, i)));
+  };
+
+  walk_tiles<DT, T, U, Tile>(segs, n_tensors, n_chunks, chunk_elems, load_tile, store_tile, generic);
+}
+
+// Pass 2 of the snapshot form.  Pass 1 has already stored the raw gradient as the next
+// reference state, so only a step that projects (or clips) has anything left to do:
+// g <- scale_g g + coef_d d_old in place, where d_old is the buffer that stopped being current
+// when the finalize step flipped *cur (read g, read d_old, write g: 3 N s bytes).
+template <int DT, int T, int U>
+__global__ __launch_bounds__(T) void snap_apply_kernel(const Seg* __restrict__ segs,
+                                                              int n_tensors, int64_t n_chunks,
+                                                              int chunk_elems,
+                                                              const gac_result* __restrict__ res,
+                                                              SnapArgs snap) {
+  constexpr int N = Elem<DT>::kPerVec;
+  if (res->nonfinite || !res->modified) return;
+  const float k = static_cast<float>(res->coef_d);
+  const float beta = static_cast<float>(res->scale_g);
+  const int64_t old_off = *snap.cur ? 0 : snap.delta;  // the buffer that is no longer current
+  const int tid = threadIdx.x;
+
+  typedef PairTile<U> Tile;
+  auto load_tile = [&](const Chunk& ch, Tile& tl) {
+    const gvec* gv = reinterpret_cast<const gvec*>(ch.a) + tid;
+    const gvec* dv = reinterpret_cast<const gvec*>(ch.b + old_off) + tid;
+#pragma unroll
+    for (int u = 0; u < U; ++u) tl.a[u] = ld16<GAC_APPLY_NT_LOAD>(gv + u * T);
+#pragma unroll
+    for (int u = 0; u < U; ++u) tl.b[u] = ld16<GAC_APPLY_NT_LOAD>(dv + u * T);
+  };
+  auto store_tile = [&](const Chunk& ch, const Tile& tl) {
+    gvec* gv = reinterpret_cast<gvec*>(const_cast<gchar*>(ch.a)) + tid;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      st16<GAC_APPLY_NT_STORE>(gv + u * T, project_vec<DT>(tl.a[u], tl.b[u], k, beta));
+  };
+  auto generic = [&](const Chunk& ch) {
+    gchar* ga = const_cast<gchar*>(ch.a);
+    gvec* gv = reinterpret_cast<gvec*>(ga);
+    const gvec* dv = reinterpret_cast<const gvec*>(ch.b + old_off);
+    const int nvec = ch.len / N;
+    for (int i = tid; i < nvec; i += T)
+      st16<GAC_APPLY_NT_STORE>(gv + i, project_vec<DT>(ld16<GAC_APPLY_NT_LOAD>(gv + i),
+                                                       ld16<GAC_APPLY_NT_LOAD>(dv + i), k, beta));
+    for (int i = nvec * N + tid; i < ch.len; i += T)
+      store_elem<DT>(ga, i, fmaf(k, load_elem<DT>(ch.b + old_off, i), beta * load_elem<DT>(ch.a, i)));
   };
 
   walk_tiles<DT, T, U, Tile>(segs, n_tensors, n_chunks, chunk_elems, load_tile, store_tile, generic);
@@ -944,23 +1069,49 @@ int adamw_blocks_per_cu(int dtype) {
 
 // ------------------------------------------------------------------ launchers
 
+namespace {
+FinalArgs final_args(const double* sums_in, double* sums_out, gac_result* dev_result,
+                     gac_result* host_result, const DecideParams& p, int mode) {
+  FinalArgs f;
+  f.sums_in = sums_in;
+  f.sums_out = sums_out;
+  f.res = dev_result;
+  f.host_res = host_result;
+  f.p = p;
+  f.mode = mode;
+  return f;
+}
+}  // namespace
+
 hipError_t launch_reduce(int dtype, const Seg* dev_segs, int64_t n_chunks, int chunk_elems,
-                         double* dev_partials, int grid, hipStream_t stream) {
-  if (dtype == GAC_F32) {
-    reduce_kernel<GAC_F32, GAC_REDUCE_THREADS, GAC_REDUCE_UNROLL>
-        <<<grid, GAC_REDUCE_THREADS, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials);
+                         double* dev_partials, unsigned int* dev_ticket, int grid, double* sums_out,
+                         gac_result* dev_result, gac_result* host_result, DecideParams p, int mode,
+                         int64_t snap_delta, hipStream_t stream) {
+  // the combine of the folded finalize step must be the one of the stand-alone kernel, bit for bit
+  static_assert(GAC_REDUCE_THREADS == kThreads, "the fixed-order combine assumes kThreads lanes");
+  const FinalArgs f = final_args(nullptr, sums_out, dev_result, host_result, p, mode | 1);
+  const SnapArgs sn = {p.cur, snap_delta};
+  constexpr int T = GAC_REDUCE_THREADS, U = GAC_REDUCE_UNROLL;
+  if (p.cur != nullptr) {
+    if (dtype == GAC_F32) {
+      reduce_kernel<GAC_F32, T, U, true><<<grid, T, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
+    } else {
+      reduce_kernel<GAC_BF16, T, U, true><<<grid, T, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
+    }
   } else {
-    reduce_kernel<GAC_BF16, GAC_REDUCE_THREADS, GAC_REDUCE_UNROLL>
-        <<<grid, GAC_REDUCE_THREADS, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials);
+    if (dtype == GAC_F32) {
+      reduce_kernel<GAC_F32, T, U, false><<<grid, T, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
+    } else {
+      reduce_kernel<GAC_BF16, T, U, false><<<grid, T, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
+    }
   }
   return hipGetLastError();
 }
 
-hipError_t launch_finalize(const double* dev_partials, int n_partials, const double* sums_in,
-                           double* sums_out, gac_result* dev_result, gac_result* host_result,
-                           DecideParams p, int mode, hipStream_t stream) {
-  finalize_kernel<<<1, kThreads, 0, stream>>>(dev_partials, n_partials, sums_in, sums_out,
-                                               dev_result, host_result, p, mode);
+hipError_t launch_finalize(const double* sums_in, double* sums_out, gac_result* dev_result,
+                           gac_result* host_result, DecideParams p, hipStream_t stream) {
+  finalize_kernel<<<1, kThreads, 0, stream>>>(
+      nullptr, 0, final_args(sums_in, sums_out, dev_result, host_result, p, /*mode=*/2));
   return hipGetLastError();
 }
 
@@ -1002,6 +1153,20 @@ hipError_t launch_exchange(int dtype, const Seg* dev_segs, int n_tensors, int64_
   return hipGetLastError();
 }
 
+hipError_t launch_snap_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
+                             int chunk_elems, const gac_result* dev_result, int32_t* dev_cur,
+                             int64_t snap_delta, int grid, hipStream_t stream) {
+  const SnapArgs sn = {dev_cur, snap_delta};
+  if (dtype == GAC_F32) {
+    snap_apply_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, sn);
+  } else {
+    snap_apply_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, sn);
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_apply_adamw(int dtype, const Seg* dev_segs, const AdamSeg* dev_adam,
                               int n_tensors, int64_t n_chunks, int chunk_elems,
                               const gac_result* dev_result, AdamScalars h, int grid,
@@ -1034,10 +1199,16 @@ hipError_t launch_sweep(const double* hist_c, const int32_t* hist_regime, int hi
 
 namespace {
 __global__ void set_step_kernel(int64_t* dev_step, int64_t value) { *dev_step = value; }
+__global__ void set_word_kernel(uint32_t* dev_word, uint32_t value) { *dev_word = value; }
 }  // namespace
 
 hipError_t launch_set_step(int64_t* dev_step, int64_t value, hipStream_t stream) {
   set_step_kernel<<<1, 1, 0, stream>>>(dev_step, value);
+  return hipGetLastError();
+}
+
+hipError_t launch_set_word(uint32_t* dev_word, uint32_t value, hipStream_t stream) {
+  set_word_kernel<<<1, 1, 0, stream>>>(dev_word, value);
   return hipGetLastError();
 }
 

@@ -37,6 +37,56 @@ def rel_l2(gpu: Sequence[torch.Tensor], want: Sequence[np.ndarray]) -> float:
     return math.sqrt(num / den) if den > 0 else math.sqrt(num)
 
 
+def check_projected_tensor(got: torch.Tensor, want: np.ndarray, x: torch.Tensor, y: torch.Tensor,
+                           k: float, beta: float, dt: int, name: str = ""):
+    """One tensor of the projected gradient against the oracle's fp64 values, element by element
+    and as a whole.  got, x (raw gradient) and y (reference state) are device tensors in the
+    storage dtype; want is the oracle's output.  The comparison itself runs in fp64 on the
+    device that holds them (the oracle's values are uploaded as they are).
+
+    Element bound, from the arithmetic of the pass (one fp32 FMA of exactly widened inputs, then
+    for bf16 storage one round-to-nearest-even to 8 significant bits):
+        |got - want| <= h |want| + 2^-22 (|beta x| + |k y|) + tiny,
+    h = 2^-8 for bf16 (half an ulp at the bottom of a binade), 2^-24 for fp32.  The second term
+    covers the fp32 roundings of beta x, of k itself and of the FMA measured against the
+    UNCANCELLED size of the two terms (where beta x and k y nearly cancel, the error is that
+    of the terms, not of their small sum), and the ~1e-9 relative difference between the
+    GPU's k and the oracle's.  Whole tensor (>= 64 elements): relative L2 within the parity
+    tolerance for the dtype.  Returns (sum of squared differences, sum of squared wants)."""
+    if got.numel() == 0:
+        return 0.0, 0.0
+    dev = got.device
+    w = torch.from_numpy(want).to(dev)
+    a = got.detach().reshape(-1).to(torch.float64)
+    mag = x.detach().reshape(-1).to(torch.float64).abs_().mul_(abs(beta))
+    mag.add_(y.detach().reshape(-1).to(torch.float64).abs_(), alpha=abs(k))
+    half_ulp, tiny = (2.0 ** -8, 2.0 ** -134) if dt == B.BF16 else (2.0 ** -24, 2.0 ** -150)
+    tol = mag.mul_(2.0 ** -22).add_(w.abs(), alpha=half_ulp).add_(tiny)
+    diff = a.sub_(w)
+    excess = float((diff.abs() - tol).max())
+    assert excess <= 0.0, f"{name}: an element is {excess:.3e} beyond its bound"
+    num, den = float(torch.dot(diff, diff)), float(torch.dot(w, w))
+    if got.numel() >= 64 and den > 0.0:
+        err = math.sqrt(num / den)
+        assert err <= GRAD_TOL[dt], f"{name}: rel-L2 {err:.3e}"
+    return num, den
+
+
+def check_projected_list(g_after, outs, g_before, d_before, s, alpha: float, beta: float, dt: int,
+                         tensors=None) -> float:
+    """Every tensor (or the given ones) through check_projected_tensor, then the list-wide
+    relative L2.  s are the oracle's three sums; k = (alpha - beta) <g,d>/<d,d> (Appendix A.2)."""
+    k = (alpha - beta) * s[0] / s[2]
+    num = den = 0.0
+    for j in (range(len(g_after)) if tensors is None else tensors):
+        n, d = check_projected_tensor(g_after[j], outs[j], g_before[j], d_before[j], k, beta, dt, f"tensor {j}")
+        num += n
+        den += d
+    err = math.sqrt(num / den) if den > 0 else math.sqrt(num)
+    assert err <= GRAD_TOL[dt], f"projected gradient rel-L2 {err}"
+    return err
+
+
 def bits_equal(a: torch.Tensor, b: torch.Tensor) -> bool:
     if a.dtype == torch.bfloat16:
         return torch.equal(a.view(torch.int16), b.view(torch.int16))
@@ -64,8 +114,7 @@ def check_step(res, g_before: Sequence[torch.Tensor], d_before: Sequence[torch.T
     if dec.regime == O.PROJECT:
         assert res.alpha == math.fabs(c_low / res.c)
         assert abs(res.alpha - dec.alpha) <= 1e-4 * dec.alpha
-        err = rel_l2(g_after, outs)
-        assert err <= GRAD_TOL[dt], f"projected gradient rel-L2 {err}"
+        check_projected_list(g_after, outs, g_before, d_before, s, dec.alpha, 1.0, dt)
     else:
         assert res.alpha == 1.0 and res.coef == 0.0
         for a, b in zip(g_after, g_before):
@@ -74,6 +123,17 @@ def check_step(res, g_before: Sequence[torch.Tensor], d_before: Sequence[torch.T
     for a, b in zip(d_after, g_before):
         assert bits_equal(a, b), "state must equal the raw gradient bitwise"
     return dec, outs
+
+
+def read_device_record(dev_addr: int) -> "B.GacResult":
+    """A gac_result record copied from device (or host-mapped) memory at a raw address."""
+    import ctypes
+    rec = B.GacResult()
+    hip = ctypes.CDLL("libamdhip64.so")  # after torch: binds to the runtime already in the process
+    hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+    rc = hip.hipMemcpy(ctypes.byref(rec), ctypes.c_void_p(dev_addr), ctypes.sizeof(rec), 2)  # device -> host
+    assert rc == 0, f"hipMemcpy failed: {rc}"
+    return rec
 
 
 def clone_list(ts: Sequence[torch.Tensor]) -> List[torch.Tensor]:

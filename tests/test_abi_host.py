@@ -4,6 +4,7 @@ include/gac.h declares, and the host logic that runs before any GPU call behaves
 import ctypes
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -28,12 +29,31 @@ def test_library_exports_every_declared_symbol():
     assert B.lib().gac_version().decode().startswith("gac-mi355x")
 
 
-def test_struct_layouts_match_header():
-    assert ctypes.sizeof(B.GacResult) == 104
-    assert ctypes.sizeof(B.GacDiag) == 80
-    assert ctypes.sizeof(B.GacAdamWHyper) == 48
-    assert ctypes.sizeof(B.GacConfig) == 96
-    assert ctypes.sizeof(B.GacPlacement) == 320
+def test_struct_layouts_match_header(tmp_path):
+    """Sizes and field offsets of the ctypes mirrors against what a C compiler makes of gac.h."""
+    structs = {"gac_config": B.GacConfig, "gac_result": B.GacResult, "gac_diag": B.GacDiag,
+               "gac_adamw_hyper": B.GacAdamWHyper, "gac_placement": B.GacPlacement}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "gac.h"', 'int main(void) {']
+    for cname, cls in structs.items():
+        lines.append(f'  printf("{cname} size %zu\\n", sizeof({cname}));')
+        for fname, _ in cls._fields_:
+            lines.append(f'  printf("{cname} {fname} %zu\\n", offsetof({cname}, {fname}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src),
+                    "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    seen = 0
+    for line in out.splitlines():
+        cname, field, value = line.split()
+        cls = structs[cname]
+        want = ctypes.sizeof(cls) if field == "size" else getattr(cls, field).offset
+        assert int(value) == want, line
+        seen += 1
+    assert seen == sum(len(c._fields_) + 1 for c in structs.values())
+    assert ctypes.sizeof(B.GacResult) == 104  # the static scratch reserves 128 bytes for it
 
 
 def test_default_config_is_the_papers():

@@ -45,17 +45,19 @@ def check_result(res, s, dec):
     assert res.regime == dec.regime and res.nonfinite == 0
 
 
-def check_projection(g_after, g_h, d_h, s, dec, dtype, tensors):
-    """rel-L2 of the GPU's projected gradient against the oracle over the given tensors."""
+def check_projection(g_after, g_raw, d_raw, g_h, d_h, s, dec, dtype, tensors):
+    """The GPU's projected gradient against the oracle over the given tensors, one tensor at a
+    time (the oracle's fp64 output of one tensor is dropped before the next is computed): every
+    element within its bound, every tensor and the whole list within the relative-L2 tolerance."""
     dt = U.code(dtype)
+    k = (dec.alpha - 1.0) * s[0] / s[2]
     num = den = 0.0
     for j in tensors:
         want = O.project_decomposed(g_h[j], d_h[j], dt, s, dec.alpha)
-        got = g_after[j].detach().to("cpu").reshape(-1).to(torch.float64).numpy()
-        diff = got - want
-        num += float(np.dot(diff, diff))
-        den += float(np.dot(want, want))
-        del want, got, diff
+        n, d = U.check_projected_tensor(g_after[j], want, g_raw[j], d_raw[j], k, 1.0, dt, f"tensor {j}")
+        num += n
+        den += d
+        del want
     err = math.sqrt(num / den)
     assert err <= U.GRAD_TOL[dt], err
     return err
@@ -76,7 +78,7 @@ def run_case(shapes, dtype, rho, config_id, c_high, expect):
     assert abs(res.c - rho) <= 5 * (1 - rho * rho) / math.sqrt(n) + 2e-3
     assert all(U.bits_equal(a, b) for a, b in zip(d, g_raw)), "state must be the raw gradient"
     if expect == B.PROJECT:
-        err = check_projection(g, g_h, d_h, s, dec, dtype, range(len(shapes)))
+        err = check_projection(g, g_raw, d0, g_h, d_h, s, dec, dtype, range(len(shapes)))
         say(f"  rho={rho} c={res.c:.6f} project rel-L2={err:.2e}")
     else:
         assert all(U.bits_equal(a, b) for a, b in zip(g, g_raw)), "gradient must be untouched"
@@ -135,12 +137,12 @@ def test_seven_billion_bf16_list_consecutive_steps():
     say("step 2: oracle sums over all elements")
     g_h, d_h, s, dec = oracle_decision(g2, g1, dtype, C_LOW, 2.0)
     check_result(res, s, dec)
-    # sampled tensors: embedding (largest), first layer q k v o gate up down norm norm, final norm
-    sample = [0] + list(range(2, 11)) + [len(shapes) - 1]
-    say("step 2: oracle projection on sampled tensors")
-    err = check_projection(g, g_h, d_h, s, dec, dtype, sample)
-    say(f"  c={res.c:.6f} alpha={res.alpha:.6f} rel-L2(sample)={err:.2e}")
+    say("step 2: oracle projection on all 255 tensors, element by element")
+    err = check_projection(g, g2, g1, g_h, d_h, s, dec, dtype, range(len(shapes)))
+    say(f"  c={res.c:.6f} alpha={res.alpha:.6f} rel-L2(all tensors)={err:.2e}")
     del g_h, d_h
+    # (steps 4-16 sample: embedding (largest), first layer q k v o gate up down norm norm, final norm)
+    sample = [0] + list(range(2, 11)) + [len(shapes) - 1]
     # properties over ALL elements (fp64 on the GPU): only the component along d changed,
     # and it was brought to sign(c) c_low |g|
     dot_gp_d = sum(float(torch.dot(a.reshape(-1).double(), b.reshape(-1).double())) for a, b in zip(g, g1))
@@ -197,7 +199,7 @@ def test_seven_billion_bf16_list_consecutive_steps():
             say("step 16: oracle sums over all elements, projection on sampled tensors")
             g_h, d_h, s, dec = oracle_decision(raw, prev_raw, dtype, C_LOW, 2.0)
             check_result(r, s, dec)
-            err = check_projection(g, g_h, d_h, s, dec, dtype, sample)
+            err = check_projection(g, raw, prev_raw, g_h, d_h, s, dec, dtype, sample)
             say(f"  c={r.c:.6f} alpha={r.alpha:.6f} rel-L2(sample)={err:.2e}")
             del g_h, d_h
         say(f"step {step}: c={r.c:.6f} {B.REGIME_NAMES[r.regime]}")
