@@ -63,7 +63,8 @@ enum {
   GAC_ERR_ALLOC = -3,          /* host or device allocation failed */
   GAC_ERR_HIP = -4,            /* a HIP runtime call failed; see gac_last_hip_error() */
   GAC_ERR_NONFINITE = -5,      /* a sum was inf/nan: nothing was modified (see gac_step) */
-  GAC_ERR_UNIMPLEMENTED = -6   /* this combination of entry point and configuration is not built */
+  GAC_ERR_UNIMPLEMENTED = -6,  /* this combination of entry point and configuration is not built */
+  GAC_ERR_TOO_LARGE = -7       /* a size exceeds a fixed capacity of the library (gac_step_static) */
 };
 
 /* gac_config.flags */
@@ -221,6 +222,34 @@ int gac_apply(gac_ctx* ctx, void* const* grad_ptrs, const double* dev_sums3, voi
 int gac_step_adamw(gac_ctx* ctx, void* const* grad_ptrs, float* const* master_p, float* const* m,
                    float* const* v, void* const* p_lowp, const gac_adamw_hyper* hyper,
                    void* hip_stream, gac_result* host_out);
+
+/* gac_step for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  No context: everything the step needs besides the caller's
+ * buffers (tensor table, per-workgroup partial sums, ticket counter, sums, result record)
+ * lives in a static device array inside the library, 57,856 bytes per GPU, held until the
+ * process ends.  The call allocates nothing on host or device, calls no hipMalloc / hipFree,
+ * copies nothing and waits for nothing: it only launches kernels on hip_stream (the tensor
+ * table travels as kernel arguments, 96 tensors per launch), so it can be captured.
+ *   cfg         thresholds, eps, beta, max_grad_norm, dtype, n_tensors, numel as for gac_init;
+ *               state_ptrs is REQUIRED (the caller owns the reference state: numel[j] elements
+ *               of dtype per tensor, zero before the first update); device as for gac_init;
+ *               flags and history_capacity must be 0; chunk_elems, grid_blocks, apply_blocks
+ *               are honoured (0 = the defaults of gac_init).
+ *               Limits: n_tensors <= GAC_STATIC_MAX_TENSORS and grid_blocks <= 1024, else
+ *               GAC_ERR_TOO_LARGE and nothing is launched.
+ *   grad_ptrs   as for gac_step (modified in place in the projection regime)
+ *   step        the number this update gets in the result record (the caller counts; the
+ *               library keeps nothing between calls)
+ *   result_out  NULL, or device-accessible memory (device memory, or host-mapped pinned memory)
+ *               that receives the gac_result when the stream gets there
+ * With the same configuration, device and inputs the gradient, the state and the result are
+ * bit-identical to gac_step's.  All calls on one GPU share the one array: calls whose kernels
+ * can overlap on that GPU (different streams, different threads) race and must be serialised
+ * by the caller.  Nothing in the array has to survive from call to call (each call rewrites
+ * the table and clears the counter it needs at zero). */
+#define GAC_STATIC_MAX_TENSORS 1024
+int gac_step_static(const gac_config* cfg, void* const* grad_ptrs, int64_t step, void* hip_stream,
+                    gac_result* result_out);
 
 /* Device address of the result of the most recent step, for callers that branch on the
  * GPU.  Valid until gac_destroy; overwritten by the next step. */

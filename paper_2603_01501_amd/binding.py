@@ -24,8 +24,10 @@ ERR_ALLOC = -3
 ERR_HIP = -4
 ERR_NONFINITE = -5
 ERR_UNIMPLEMENTED = -6
+ERR_TOO_LARGE = -7
 
 FLAG_SNAPSHOT_IN_REDUCE = 1
+STATIC_MAX_TENSORS = 1024
 
 
 class GacConfig(ctypes.Structure):
@@ -130,6 +132,7 @@ def lib() -> ctypes.CDLL:
         "gac_last_hip_error": (ctypes.c_char_p, [vp]),
         "gac_version": (ctypes.c_char_p, []),
         "gac_source_hash": (ctypes.c_char_p, []),
+        "gac_step_static": (ctypes.c_int, [ctypes.POINTER(GacConfig), vpp, ctypes.c_int64, vp, vp]),
     }
     for name, (res, args) in sig.items():
         f = getattr(L, name)
@@ -197,6 +200,20 @@ def make_config(numel: Sequence[int], dtype: int, c_low: float = 0.05, c_high: f
     cfg.apply_blocks = apply_blocks
     cfg.max_grad_norm, cfg.history_capacity, cfg.flags = max_grad_norm, history_capacity, flags
     return cfg, (numel_arr, state_ptrs)
+
+
+def gac_step_static(cfg: GacConfig, grads: Sequence, step: int, result_out=None, stream=None) -> int:
+    """The step that allocates nothing (no context).  ``cfg`` comes from make_config with
+    ``state`` given; ``result_out`` is None or a device-accessible buffer of at least
+    ctypes.sizeof(GacResult) bytes (a torch uint8 tensor, or an address).  Only enqueues work;
+    returns the C return code after raising on errors."""
+    if result_out is not None and hasattr(result_out, "data_ptr"):
+        result_out = result_out.data_ptr()
+    rc = lib().gac_step_static(ctypes.byref(cfg), ptr_list(grads), step, _stream_handle(stream),
+                               ctypes.c_void_p(result_out) if result_out else None)
+    if rc != OK:
+        raise GacError(rc, lib().gac_last_hip_error(None).decode())
+    return rc
 
 
 class Gac:

@@ -487,6 +487,10 @@ int init_impl(gac_ctx** out, const gac_config* cfg) {
   if (dev < 0) GAC_HIP(ctx, hipGetDevice(&dev));
   ctx->device = dev;
   DeviceGuard guard(dev);
+  {  // set-up for gac_step_static: resolve this device's copy of the static array once, here
+    gac::StaticScratch sc;
+    GAC_HIP(ctx, gac::static_scratch(dev, &sc));
+  }
   hipDeviceProp_t prop;
   GAC_HIP(ctx, hipGetDeviceProperties(&prop, dev));
   auto pick_grid = [&](int requested, int64_t by_default) {
@@ -1106,6 +1110,119 @@ int gac_profile_read(gac_ctx* ctx, double* ms_reduce, double* ms_finalize, doubl
   return GAC_OK;
 }
 
+// ---- gac_step_static: the step for callers that cannot allocate (see gac.h) ----------------
+namespace {
+// Grid defaults are per device; looked up once (no allocation) and kept.
+constexpr int kMaxDevicesStatic = 64;
+int g_static_cus[kMaxDevicesStatic] = {};
+
+int static_step_impl(const gac_config* cfg, void* const* grad_ptrs, int64_t step,
+                     hipStream_t stream, gac_result* result_out) {
+  if (cfg == nullptr || cfg->n_tensors < 0 || (cfg->n_tensors > 0 && (cfg->numel == nullptr ||
+      cfg->state_ptrs == nullptr || grad_ptrs == nullptr)) || cfg->flags != 0 || cfg->reserved != 0 ||
+      cfg->history_capacity != 0 || cfg->grid_blocks < 0 || cfg->apply_blocks < 0 ||
+      cfg->apply_blocks > gac::kMaxGridBlocks || step < 0)
+    return GAC_ERR_INVALID_ARG;
+  if (cfg->n_tensors > gac::kStaticMaxTensors || cfg->grid_blocks > gac::kStaticMaxGrid)
+    return GAC_ERR_TOO_LARGE;
+  if (!thresholds_ok(cfg->c_low, cfg->c_high) || !(cfg->eps >= 0.0) || !(cfg->beta >= 0.0) ||
+      !std::isfinite(cfg->eps) || !std::isfinite(cfg->beta) || !(cfg->max_grad_norm >= 0.0))
+    return GAC_ERR_BAD_THRESHOLDS;
+  int chunk_elems = 0;
+  int rc = resolve_chunk_elems(cfg->dtype, cfg->chunk_elems, &chunk_elems);
+  if (rc != GAC_OK) return rc;
+  const int n = cfg->n_tensors;
+  const uintptr_t es = static_cast<uintptr_t>(elem_size(cfg->dtype));
+  int64_t n_chunks = 0;
+  for (int j = 0; j < n; ++j) {
+    if (cfg->numel[j] < 0) return GAC_ERR_INVALID_ARG;
+    const uintptr_t g = reinterpret_cast<uintptr_t>(grad_ptrs[j]);
+    const uintptr_t d = reinterpret_cast<uintptr_t>(cfg->state_ptrs[j]);
+    if (cfg->numel[j] > 0 && (g == 0 || d == 0 || g == d)) return GAC_ERR_INVALID_ARG;
+    if (g % es != 0 || d % es != 0) return GAC_ERR_INVALID_ARG;
+    n_chunks += (cfg->numel[j] + chunk_elems - 1) / chunk_elems;
+  }
+
+  // ---- from here on the GPU is touched
+  int dev = cfg->device;
+  if (dev < 0) GAC_HIP(nullptr, hipGetDevice(&dev));
+  if (dev >= kMaxDevicesStatic) return GAC_ERR_INVALID_ARG;
+  DeviceGuard guard(dev);
+  gac::StaticScratch sc;
+  GAC_HIP(nullptr, gac::static_scratch(dev, &sc));
+  if (g_static_cus[dev] == 0) {
+    int cus = 0;
+    GAC_HIP(nullptr, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    g_static_cus[dev] = cus > 0 ? cus : 1;
+  }
+  const int64_t cus = g_static_cus[dev];
+  auto pick_grid = [&](int requested, int64_t by_default, int64_t cap) {
+    int64_t g = requested > 0 ? requested : by_default;
+    if (g > n_chunks) g = n_chunks;
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return static_cast<int>(g);
+  };
+  // the same defaults as gac_init, so that the partial sums (and with them every bit of the
+  // result) are those of gac_step
+  const int grid = pick_grid(cfg->grid_blocks, cus, gac::kStaticMaxGrid);
+  const int grid_apply = pick_grid(cfg->apply_blocks, cus * 3 / 4, gac::kMaxGridBlocks);
+
+  // The tensor table goes to the device as kernel arguments, a batch at a time; the first
+  // batch also clears the ticket counter (an earlier call that was cut short may have left it
+  // anywhere).
+  gac::SegBatch batch;
+  int64_t c = 0;
+  int filled = 0;
+  bool first_batch = true;
+  auto flush = [&](int first) -> int {
+    batch.first = first;
+    batch.count = filled;
+    GAC_HIP(nullptr, gac::launch_fill_segs(sc.segs, batch, first_batch ? sc.ticket : nullptr, stream));
+    first_batch = false;
+    filled = 0;
+    return GAC_OK;
+  };
+  int batch_first = 0;
+  for (int j = 0; j <= n; ++j) {  // entry n is the sentinel
+    Seg& e = batch.e[filled];
+    e.a = j < n ? grad_ptrs[j] : nullptr;
+    e.b = j < n ? cfg->state_ptrs[j] : nullptr;
+    e.numel = j < n ? cfg->numel[j] : 0;
+    e.first_chunk = c;
+    if (j < n) c += (cfg->numel[j] + chunk_elems - 1) / chunk_elems;
+    if (++filled == gac::kSegBatch || j == n) {
+      rc = flush(batch_first);
+      if (rc != GAC_OK) return rc;
+      batch_first = j + 1;
+    }
+  }
+
+  DecideParams p;
+  p.c_low = cfg->c_low;
+  p.c_high = cfg->c_high;
+  p.eps = cfg->eps;
+  p.beta = cfg->beta;
+  p.max_grad_norm = cfg->max_grad_norm;
+  p.step = nullptr;
+  p.hist_c = nullptr;
+  p.hist_regime = nullptr;
+  p.hist_cap = 0;
+  p.step_value = step;
+  p.cur = nullptr;
+  GAC_HIP(nullptr, gac::launch_reduce(cfg->dtype, sc.segs, n_chunks, chunk_elems, sc.partials, sc.ticket,
+                                      grid, sc.sums, sc.result, result_out, p, /*mode=*/2, 0, stream));
+  GAC_HIP(nullptr, gac::launch_apply(cfg->dtype, sc.segs, n, n_chunks, chunk_elems, sc.result,
+                                     grid_apply, stream));
+  return GAC_OK;
+}
+}  // namespace
+
+int gac_step_static(const gac_config* cfg, void* const* grad_ptrs, int64_t step, void* hip_stream,
+                    gac_result* result_out) {
+  return static_step_impl(cfg, grad_ptrs, step, static_cast<hipStream_t>(hip_stream), result_out);
+}
+
 const char* gac_strerror(int code) {
   switch (code) {
     case GAC_OK: return "ok";
@@ -1115,6 +1232,7 @@ const char* gac_strerror(int code) {
     case GAC_ERR_HIP: return "HIP runtime error";
     case GAC_ERR_NONFINITE: return "non-finite gradient statistics; nothing was modified";
     case GAC_ERR_UNIMPLEMENTED: return "not implemented for this configuration";
+    case GAC_ERR_TOO_LARGE: return "size exceeds a fixed capacity of the library (see gac_step_static)";
     default: return "unknown error code";
   }
 }

@@ -126,4 +126,30 @@ hipError_t launch_set_word(uint32_t* dev_word, uint32_t value, hipStream_t strea
 hipError_t launch_state_op(int dtype, int op, const Seg* dev_segs, int64_t n_chunks,
                            int chunk_elems, int grid, hipStream_t stream);
 
+// The entry point that allocates nothing keeps its device-side working memory in a static
+// device array (one copy per GPU).  Limits of that array:
+constexpr int kStaticMaxTensors = GAC_STATIC_MAX_TENSORS;
+constexpr int kStaticMaxGrid = 1024;  // partial-sum slots
+struct StaticScratch {
+  unsigned int* ticket;
+  double* sums;
+  gac_result* result;
+  double* partials;
+  Seg* segs;
+};
+// Device addresses of the parts of the static array on `device`, which must be the current
+// device (the array's address is looked up once per device and kept).
+hipError_t static_scratch(int device, StaticScratch* out);
+size_t static_scratch_bytes();
+
+// A batch of tensor-table entries small enough to travel as a kernel argument.
+constexpr int kSegBatch = 96;
+struct SegBatch {
+  int32_t first, count;
+  Seg e[kSegBatch];
+};
+// table[first + i] = e[i]; with ticket_to_clear not null also *ticket_to_clear = 0.
+hipError_t launch_fill_segs(Seg* dev_table, const SegBatch& batch, unsigned int* ticket_to_clear,
+                            hipStream_t stream);
+
 }  // namespace gac

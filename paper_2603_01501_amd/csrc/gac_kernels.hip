@@ -25,6 +25,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "gac_internal.h"
 
 namespace gac {
@@ -1200,6 +1202,16 @@ hipError_t launch_sweep(const double* hist_c, const int32_t* hist_regime, int hi
 namespace {
 __global__ void set_step_kernel(int64_t* dev_step, int64_t value) { *dev_step = value; }
 __global__ void set_word_kernel(uint32_t* dev_word, uint32_t value) { *dev_word = value; }
+
+// Writes `count` entries of the tensor table from the kernel's own arguments (so the table
+// reaches the device without a copy command and without staging memory) and, with the first
+// batch, clears the ticket counter of the reduction.
+__global__ __launch_bounds__(kSegBatch) void fill_segs_kernel(Seg* __restrict__ table, SegBatch b,
+                                                              unsigned int* __restrict__ ticket) {
+  const int i = threadIdx.x;
+  if (i < b.count) table[b.first + i] = b.e[i];
+  if (ticket != nullptr && i == 0) *ticket = 0u;
+}
 }  // namespace
 
 hipError_t launch_set_step(int64_t* dev_step, int64_t value, hipStream_t stream) {
@@ -1210,6 +1222,64 @@ hipError_t launch_set_step(int64_t* dev_step, int64_t value, hipStream_t stream)
 hipError_t launch_set_word(uint32_t* dev_word, uint32_t value, hipStream_t stream) {
   set_word_kernel<<<1, 1, 0, stream>>>(dev_word, value);
   return hipGetLastError();
+}
+
+hipError_t launch_fill_segs(Seg* dev_table, const SegBatch& batch, unsigned int* ticket_to_clear,
+                            hipStream_t stream) {
+  fill_segs_kernel<<<1, kSegBatch, 0, stream>>>(dev_table, batch, ticket_to_clear);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ static scratch
+
+// Device memory of the entry point that allocates nothing (gac_step_static): the tensor
+// table, the per-workgroup partial sums, the ticket counter, the three sums and the result
+// record that the context-based entry points keep in memory from hipMalloc.  Every GPU the
+// library runs on holds its own copy of this array, at its own address, until the process
+// ends.  In host code the name is only a handle for hipGetSymbolAddress: the address that
+// kernels can use is looked up once per device and kept in g_scratch_ptr.
+namespace {
+constexpr size_t kScratchTicketOff = 0;
+constexpr size_t kScratchSumsOff = 64;
+constexpr size_t kScratchResultOff = 128;
+constexpr size_t kScratchPartialsOff = 256;
+constexpr size_t kScratchSegsOff = kScratchPartialsOff + sizeof(double) * 3 * kStaticMaxGrid;
+constexpr size_t kScratchBytes =
+    (kScratchSegsOff + sizeof(Seg) * (kStaticMaxTensors + 1) + 255) / 256 * 256;
+static_assert(sizeof(gac_result) <= kScratchPartialsOff - kScratchResultOff, "result slot too small");
+static_assert(kScratchSegsOff % 32 == 0, "tensor table alignment");
+
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+size_t static_scratch_bytes() { return kScratchBytes; }
+
+hipError_t static_scratch(int device, StaticScratch* out) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  void* base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device] == nullptr) {
+      // `device` is the current device here: the symbol resolves to this GPU's copy
+      void* ptr = nullptr;
+      const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+      if (e != hipSuccess) return e;
+      if (ptr == nullptr) return hipErrorInvalidSymbol;
+      g_scratch_ptr[device] = ptr;
+    }
+    base = g_scratch_ptr[device];
+  }
+  unsigned char* b = static_cast<unsigned char*>(base);
+  out->ticket = reinterpret_cast<unsigned int*>(b + kScratchTicketOff);
+  out->sums = reinterpret_cast<double*>(b + kScratchSumsOff);
+  out->result = reinterpret_cast<gac_result*>(b + kScratchResultOff);
+  out->partials = reinterpret_cast<double*>(b + kScratchPartialsOff);
+  out->segs = reinterpret_cast<Seg*>(b + kScratchSegsOff);
+  return hipSuccess;
 }
 
 hipError_t launch_state_op(int dtype, int op, const Seg* dev_segs, int64_t n_chunks,
