@@ -22,6 +22,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # deliberately broken copy of the source (built into a temporary library).
 _SRC = os.environ.get("GAC_ORACLE_SRC", os.path.join(_HERE, "gac_oracle.cpp"))
 _LIB = os.environ.get("GAC_ORACLE_LIB", os.path.join(_HERE, "libgac_oracle.so"))
+# GAC_ORACLE_CXXFLAGS adds compiler flags (the sanitizer test builds an instrumented copy).
+_EXTRA_FLAGS = os.environ.get("GAC_ORACLE_CXXFLAGS", "").split()
 
 F32 = 0
 BF16 = 1
@@ -32,7 +34,7 @@ def build(force: bool = False) -> str:
     """Compile the oracle with the host compiler (no GPU toolchain involved)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
-               "-fno-fast-math", "-o", _LIB, _SRC]
+               "-fno-fast-math"] + _EXTRA_FLAGS + ["-o", _LIB, _SRC]
         subprocess.run(cmd, check=True)
     return _LIB
 

@@ -26,6 +26,7 @@
 #include <hip/hip_runtime.h>
 
 #include <mutex>
+#include <type_traits>
 
 #include "gac_internal.h"
 
@@ -70,6 +71,21 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #endif
 #ifndef GAC_REDUCE_NT_LOAD
 #define GAC_REDUCE_NT_LOAD 1
+#endif
+#ifndef GAC_SNAP_THREADS
+#define GAC_SNAP_THREADS GAC_REDUCE_THREADS
+#endif
+#ifndef GAC_SNAP_UNROLL
+#define GAC_SNAP_UNROLL GAC_REDUCE_UNROLL
+#endif
+#ifndef GAC_SNAP_DEPTH
+#define GAC_SNAP_DEPTH 2
+#endif
+#ifndef GAC_REDUCE_DEPTH
+#define GAC_REDUCE_DEPTH 1
+#endif
+#ifndef GAC_SNAP_NT_STORE
+#define GAC_SNAP_NT_STORE 1
 #endif
 #ifndef GAC_APPLY_THREADS
 #define GAC_APPLY_THREADS 512
@@ -244,16 +260,20 @@ __device__ __forceinline__ void block_sum3(double (&s)[3]) {
 
 // ------------------------------------------------------------------ finalize
 
-// Adds the per-workgroup partial sums in a fixed order: lane j takes partials j, j+T, ...,
-// then a fixed tree over lanes and waves.  The result is valid in thread 0.
+// Adds the per-workgroup partial sums in a fixed order: lane j < kThreads takes partials j,
+// j + kThreads, ..., then a fixed tree over lanes and waves (lanes beyond kThreads, in a wider
+// workgroup, add zeros, which changes no bit).  The result is valid in thread 0.
 template <int T>
 __device__ __forceinline__ void combine_partials(const double* __restrict__ partials, int n_partials,
                                                  double (&s)[3]) {
+  static_assert(T >= kThreads, "the combine is defined over kThreads lanes");
   s[0] = s[1] = s[2] = 0.0;
-  for (int j = threadIdx.x; j < n_partials; j += T) {
-    s[0] += partials[3 * j + 0];
-    s[1] += partials[3 * j + 1];
-    s[2] += partials[3 * j + 2];
+  if (threadIdx.x < kThreads) {
+    for (int j = threadIdx.x; j < n_partials; j += kThreads) {
+      s[0] += partials[3 * j + 0];
+      s[1] += partials[3 * j + 1];
+      s[2] += partials[3 * j + 2];
+    }
   }
   block_sum3<T>(s);
 }
@@ -402,7 +422,7 @@ struct SnapArgs {
 // that all partial sums have been written, adds them in the fixed order and does what follows
 // the sums (FinalArgs), so the step needs no separate finalize launch.  It also puts the
 // ticket counter back to zero for the next launch.
-template <int DT, int T, int U, bool SNAP>
+template <int DT, int T, int U, int LD, bool SNAP>
 __global__ __launch_bounds__(T) void reduce_kernel(const Seg* __restrict__ segs,
                                                           int64_t n_chunks, int chunk_elems,
                                                           double* __restrict__ partials,
@@ -437,34 +457,46 @@ __global__ __launch_bounds__(T) void reduce_kernel(const Seg* __restrict__ segs,
       gvec* __restrict__ sv = reinterpret_cast<gvec*>(ch.b + spare_off);
       const int nvec = ch.len / N;
       int i = tid;
-      for (; i + (U - 1) * T < nvec; i += U * T) {
-        u32x4 a[U], b[U];
+      // One group = U vectors per array and lane: products and their sum in fp32, then one
+      // fp64 accumulation.  LD groups are loaded before any of them is used (more bytes in
+      // flight, which a pass that also stores needs); the arithmetic and its order are those
+      // of LD = 1, so the sums do not depend on LD.
+      auto groups = [&](auto depth) {
+        constexpr int D = decltype(depth)::value;
+        for (; i + (D * U - 1) * T < nvec; i += D * U * T) {
+          u32x4 a[D * U], b[D * U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) a[u] = ld16<GAC_REDUCE_NT_LOAD>(gv + i + u * T);
+          for (int u = 0; u < D * U; ++u) a[u] = ld16<GAC_REDUCE_NT_LOAD>(gv + i + u * T);
 #pragma unroll
-        for (int u = 0; u < U; ++u) b[u] = ld16<GAC_REDUCE_NT_LOAD>(dv + i + u * T);
-        if constexpr (SNAP) {
+          for (int u = 0; u < D * U; ++u) b[u] = ld16<GAC_REDUCE_NT_LOAD>(dv + i + u * T);
+          if constexpr (SNAP) {
 #pragma unroll
-          for (int u = 0; u < U; ++u) st16<1>(sv + i + u * T, a[u]);
+            for (int u = 0; u < D * U; ++u) st16<GAC_SNAP_NT_STORE>(sv + i + u * T, a[u]);
+          }
+#pragma unroll
+          for (int grp = 0; grp < D; ++grp) {
+            float gd = 0.f, gg = 0.f, dd = 0.f;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+              float pgd = 0.f, pgg = 0.f, pdd = 0.f;
+              dot3<DT>(a[grp * U + u], b[grp * U + u], pgd, pgg, pdd);
+              gd += pgd;
+              gg += pgg;
+              dd += pdd;
+            }
+            acc[0] += static_cast<double>(gd);
+            acc[1] += static_cast<double>(gg);
+            acc[2] += static_cast<double>(dd);
+          }
         }
-        float gd = 0.f, gg = 0.f, dd = 0.f;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          float pgd = 0.f, pgg = 0.f, pdd = 0.f;
-          dot3<DT>(a[u], b[u], pgd, pgg, pdd);
-          gd += pgd;
-          gg += pgg;
-          dd += pdd;
-        }
-        acc[0] += static_cast<double>(gd);
-        acc[1] += static_cast<double>(gg);
-        acc[2] += static_cast<double>(dd);
-      }
+      };
+      if constexpr (LD > 1) groups(std::integral_constant<int, LD>{});
+      groups(std::integral_constant<int, 1>{});
       for (; i < nvec; i += T) {
         float gd = 0.f, gg = 0.f, dd = 0.f;
         const u32x4 a = ld16<GAC_REDUCE_NT_LOAD>(gv + i);
         dot3<DT>(a, ld16<GAC_REDUCE_NT_LOAD>(dv + i), gd, gg, dd);
-        if constexpr (SNAP) st16<1>(sv + i, a);
+        if constexpr (SNAP) st16<GAC_SNAP_NT_STORE>(sv + i, a);
         acc[0] += static_cast<double>(gd);
         acc[1] += static_cast<double>(gg);
         acc[2] += static_cast<double>(dd);
@@ -1095,16 +1127,17 @@ hipError_t launch_reduce(int dtype, const Seg* dev_segs, int64_t n_chunks, int c
   const SnapArgs sn = {p.cur, snap_delta};
   constexpr int T = GAC_REDUCE_THREADS, U = GAC_REDUCE_UNROLL;
   if (p.cur != nullptr) {
+    constexpr int TS = GAC_SNAP_THREADS, US = GAC_SNAP_UNROLL;
     if (dtype == GAC_F32) {
-      reduce_kernel<GAC_F32, T, U, true><<<grid, T, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
+      reduce_kernel<GAC_F32, TS, US, GAC_SNAP_DEPTH, true><<<grid, TS, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
     } else {
-      reduce_kernel<GAC_BF16, T, U, true><<<grid, T, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
+      reduce_kernel<GAC_BF16, TS, US, GAC_SNAP_DEPTH, true><<<grid, TS, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
     }
   } else {
     if (dtype == GAC_F32) {
-      reduce_kernel<GAC_F32, T, U, false><<<grid, T, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
+      reduce_kernel<GAC_F32, T, U, GAC_REDUCE_DEPTH, false><<<grid, T, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
     } else {
-      reduce_kernel<GAC_BF16, T, U, false><<<grid, T, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
+      reduce_kernel<GAC_BF16, T, U, GAC_REDUCE_DEPTH, false><<<grid, T, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
     }
   }
   return hipGetLastError();
