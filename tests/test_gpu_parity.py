@@ -164,22 +164,120 @@ def test_threshold_boundaries_are_inclusive():
         ctx.gac_set_thresholds(0.3, 0.3)
 
 
-def test_general_beta_gain():
-    """Eq. 3 with beta != 1: g' = alpha g_par + beta g_perp in the projection regime."""
-    shapes = [(30000,), (77,)]
-    g, d0 = make(shapes, torch.float32, 0.2, config_id=14)
-    d = U.clone_list(d0)
-    ctx = new_ctx(shapes, torch.float32, state=d, beta=0.5)
-    ctx.gac_state_import(d0, 0)
-    g0 = U.clone_list(g)
-    res = ctx.gac_step(g)
-    torch.cuda.synchronize()
-    assert res.regime == B.PROJECT
-    g_h, d_h = U.host_copies(g0), U.host_copies(d0)
-    s = O.sums(g_h, d_h, O.F32)
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+@pytest.mark.parametrize("beta", [0.5, 1.25])
+def test_general_beta_gain(dtype, beta):
+    """Eq. 3 with beta != 1: g' = alpha g_par + beta g_perp in the projection regime, through
+    the in-place form, the buffer-exchange form and the form fused with AdamW; nothing is
+    rescaled outside the projection regime whatever beta is."""
+    shapes = [(30000,), (77,), (2049,), (0,), (40001,)]
+    numel = [W.numel(x) for x in shapes]
+    dt = U.code(dtype)
+    g, d0 = make(shapes, dtype, 0.2, config_id=14, std=1e-3)
+    g_h, d_h = U.host_copies(g), U.host_copies(d0)
+    s = O.sums(g_h, d_h, dt)
     dec = O.decide(s, C_LOW, C_HIGH, EPS)
-    want = [O.project_decomposed(a, b, O.F32, s, dec.alpha, 0.5) for a, b in zip(g_h, d_h)]
-    assert U.rel_l2(g, want) <= 1e-5
+    assert dec.regime == O.PROJECT
+    want = [O.project_decomposed(a, b, dt, s, dec.alpha, beta) for a, b in zip(g_h, d_h)]
+    k = (dec.alpha - beta) * s[0] / s[2]
+
+    # in place
+    d = U.clone_list(d0)
+    ctx = new_ctx(shapes, dtype, state=d, beta=beta)
+    ctx.gac_state_import(d0, 0)
+    g1 = U.clone_list(g)
+    res = ctx.gac_step(g1)
+    torch.cuda.synchronize()
+    assert res.regime == B.PROJECT and res.scale_g == beta
+    assert res.coef == pytest.approx(k, rel=1e-6)
+    U.check_projected_list(g1, want, g, d0, s, dec.alpha, beta, dt)
+    assert all(U.bits_equal(a, b) for a, b in zip(d, g))
+
+    # buffer exchange: the same bits arrive in the returned buffers
+    d2 = U.clone_list(d0)
+    ctx2 = new_ctx(shapes, dtype, state=d2, beta=beta)
+    ctx2.gac_state_import(d0, 0)
+    mine = U.clone_list(g)
+    res2, returned = ctx2.gac_step_exchange(mine)
+    torch.cuda.synchronize()
+    assert (res2.c, res2.coef, res2.scale_g) == (res.c, res.coef, res.scale_g)
+    assert all(U.bits_equal(a, b) for a, b in zip(returned, g1))
+    assert all(U.bits_equal(a, b) for a, b in zip(mine, g))
+
+    # fused with AdamW: the optimizer consumes the same g' (never stored)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(6)
+    p = [torch.randn(x, generator=gen, device=DEV) * 0.02 for x in shapes]
+    m = [torch.randn(x, generator=gen, device=DEV) * 1e-4 for x in shapes]
+    v = [torch.rand(x, generator=gen, device=DEV) * 1e-6 for x in shapes]
+    p0, m0, v0 = U.clone_list(p), U.clone_list(m), U.clone_list(v)
+    d3 = U.clone_list(d0)
+    ctx3 = new_ctx(shapes, dtype, state=d3, beta=beta)
+    ctx3.gac_state_import(d0, 0)
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps_adam=1e-8, weight_decay=1e-2)
+    g3 = U.clone_list(g)
+    res3 = ctx3.gac_step_adamw(g3, p, m, v, None, t_adam=3, **hp)
+    torch.cuda.synchronize()
+    assert (res3.c, res3.coef, res3.scale_g) == (res.c, res.coef, res.scale_g)
+    assert all(U.bits_equal(a, b) for a, b in zip(g3, g))
+    for j, n in enumerate(numel):
+        if not n:
+            continue
+        pj, mj, vj = (W.to_oracle_array(t[j]) for t in (p0, m0, v0))
+        po, mo, vo = O.adamw(want[j], pj, mj, vj, 1e-3, 0.9, 0.999, 1e-8, 1e-2, 3)
+        pg, mg, vg = (t[j].cpu().reshape(-1).double().numpy() for t in (p, m, v))
+        assert np.linalg.norm(mg - mo) <= 1e-6 * np.linalg.norm(mo)
+        assert np.linalg.norm(vg - vo) <= 1e-6 * np.linalg.norm(vo)
+        tol = U.adamw_param_tolerance(pj, mj, vo, want[j], 1e-3, 0.9, 0.999, 1e-8, 3)
+        assert np.max(np.abs(pg - po) - tol) <= 0.0
+
+    # safe and violation regimes: beta plays no part
+    for rho, regime in ((0.0, B.SAFE), (0.9, B.SKIP)):
+        gs, ds0 = make(shapes, dtype, rho, config_id=19, std=1e-3)
+        ds = U.clone_list(ds0)
+        c = new_ctx(shapes, dtype, state=ds, beta=beta)
+        c.gac_state_import(ds0, 0)
+        step_and_check(c, gs, ds, dtype, expect=regime)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_cosine_is_invariant_under_power_of_two_scalings(dtype):
+    """Appendix A.1: c is a ratio of inner products, so scaling g and d by powers of two
+    changes nothing; with eps = 0 not even a bit, as long as products and squares stay inside
+    the fp32 exponent range (the products are formed in fp32).  Far outside it the documented
+    limits apply: squares that underflow give c = 0 (safe), squares that overflow are reported
+    as a non-finite step."""
+    shapes = [(50000,), (77,), (4097,)]
+    dt = U.code(dtype)
+    g0, d0 = make(shapes, dtype, 0.2, config_id=18, std=1e-3)
+    seen = {}
+    for e_g, e_d in ((0, 0), (-40, -40), (40, 40), (-40, 40), (30, -35)):
+        g = [t * 2.0 ** e_g for t in g0]
+        d = [t * 2.0 ** e_d for t in d0]
+        ctx = new_ctx(shapes, dtype, state=U.clone_list(d), eps=0.0)
+        ctx.gac_state_import(d, 0)
+        g_in = U.clone_list(g)
+        res = ctx.gac_step(g_in)
+        torch.cuda.synchronize()
+        s = O.sums(U.host_copies(g), U.host_copies(d), dt)
+        dec = O.decide(s, C_LOW, C_HIGH, 0.0)
+        assert abs(res.c - dec.c) <= U.COS_TOL and res.regime == dec.regime == B.PROJECT
+        assert res.dot == pytest.approx(s[0], rel=1e-6) and res.gg == pytest.approx(s[1], rel=1e-6)
+        seen[(e_g, e_d)] = res.c
+        want = [O.project_decomposed(a, b, dt, s, dec.alpha) for a, b in zip(U.host_copies(g), U.host_copies(d))]
+        U.check_projected_list(g_in, want, g, d, s, dec.alpha, 1.0, dt)
+    assert len(set(seen.values())) == 1, seen
+    # the documented limits (default eps): squares below the fp32 range vanish, above it overflow
+    tiny = [t * 2.0 ** -70 for t in g0]
+    ctx = new_ctx(shapes, dtype, state=U.clone_list(d0))
+    ctx.gac_state_import(d0, 0)
+    res = ctx.gac_step(U.clone_list(tiny))
+    assert res.gg == 0.0 and res.dot != 0.0 and res.regime == B.SAFE
+    huge = [t * 2.0 ** 75 for t in g0]
+    assert all(bool(torch.isfinite(t).all()) for t in huge)
+    r = B.GacResult()
+    assert B.lib().gac_step(ctx._ctx, B.ptr_list(huge), None, ctypes.byref(r)) == B.ERR_NONFINITE
+    assert r.nonfinite == 1 and r.regime == B.SKIP
 
 
 # ------------------------------------------------------------------ determinism, pointers, async
@@ -436,6 +534,45 @@ def test_async_step_replayed_from_a_hip_graph():
     assert first == 1 and len(c_hist) == 6
     assert list(zip(c_hist[1:], r_hist[1:])) == seen
     assert B.PROJECT in r_hist
+
+
+def test_thresholds_are_frozen_into_a_captured_graph():
+    """Thresholds are launch arguments: a replayed graph keeps the pair it was captured with,
+    an eager call after gac_set_thresholds uses the new pair."""
+    dtype = torch.float32
+    shapes = [(50000,), (33,)]
+    g0, d0 = make(shapes, dtype, 0.2, config_id=26)
+    d = U.clone_list(d0)
+    g = U.clone_list(g0)
+    ctx = new_ctx(shapes, dtype, state=d)          # (0.05, 0.3): c = 0.2 is projected
+    ctx.gac_state_import(d0, 0)
+    ctx.gac_step(g, sync=False)                    # eager first: uploads the pointer table
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        ctx.gac_step(g, stream=torch.cuda.current_stream(), sync=False)
+    ctx.gac_set_thresholds(0.25, 0.9)              # under these c = 0.2 is safe
+
+    def restore():
+        for a, b in zip(g, g0):
+            a.copy_(b)
+        for a, b in zip(d, d0):
+            a.copy_(b)
+        torch.cuda.synchronize()
+
+    for _ in range(2):
+        restore()
+        graph.replay()
+        torch.cuda.synchronize()
+        rec = U.read_device_record(ctx.gac_result_device())
+        assert rec.regime == B.PROJECT and rec.alpha == C_LOW / abs(rec.c)   # the captured pair
+        assert not U.bits_equal(g[0], g0[0])
+        restore()
+        res = ctx.gac_step(g)                                               # the new pair
+        torch.cuda.synchronize()
+        assert res.regime == B.SAFE and res.c == rec.c
+        assert all(U.bits_equal(a, b) for a, b in zip(g, g0))
 
 
 def test_gradient_buffer_that_is_the_state_buffer_is_rejected():
