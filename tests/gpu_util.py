@@ -140,13 +140,74 @@ def clone_list(ts: Sequence[torch.Tensor]) -> List[torch.Tensor]:
     return [t.clone() for t in ts]
 
 
+# Relative error allowed on the AdamW step (measured against its uncancelled size): about ten
+# fp32 roundings (moments, square root, scaling, sum, division, step size) of 2^-24 each, plus
+# half the relative error of the second moment.
+ADAMW_STEP_RTOL = 2e-6
+
+
 def adamw_param_tolerance(p_old: np.ndarray, m_old: np.ndarray, v_new: np.ndarray, g: np.ndarray,
                           lr: float, beta1: float, beta2: float, eps_adam: float, t: int) -> np.ndarray:
     """Element-wise bound for an fp32 AdamW parameter against the fp64 oracle: two roundings of
-    the parameter (2 ulp) plus 1e-5 of the step evaluated with |m| and |g| - the first moment
+    the parameter (2 ulp) plus ADAMW_STEP_RTOL of the step evaluated with |m| and |g| - the first moment
     b1 m + (1-b1) g can cancel, and then the fp32 rounding of its two terms, not the size of
     the step itself, sets the error."""
     bc1, bc2 = 1.0 - beta1 ** t, 1.0 - beta2 ** t
     step_abs = lr * (beta1 * np.abs(m_old.astype(np.float64)) + (1.0 - beta1) * np.abs(g)) / bc1 / \
         (np.sqrt(v_new / bc2) + eps_adam)
-    return 2.0 * np.spacing(np.abs(p_old)).astype(np.float64) + 1e-5 * step_abs
+    return 2.0 * np.spacing(np.abs(p_old)).astype(np.float64) + ADAMW_STEP_RTOL * step_abs
+
+
+def check_adamw_tensor(p_new, m_new, v_new, po, mo, vo, p_old, m_old, v_old, x, y, k: float, beta: float,
+                       lr: float, beta1: float, beta2: float, eps_adam: float, t: int, name: str = ""):
+    """One tensor (or a slice of one) of the fused pass's optimizer state against the oracle's
+    unfused composition, element by element, compared in fp64 on the device that holds the
+    tensors.  p_new, m_new, v_new: fp32 device tensors after the step; po, mo, vo: the oracle's
+    fp64 outputs (numpy); p_old, m_old, v_old: fp32 device tensors before the step; x, y: raw
+    gradient and reference state (storage dtype, device).
+
+    Bounds, from the kernel's arithmetic (every operation once in fp32, inputs exact).  With
+    G = |beta x| + |k y| the uncancelled size of g' (its fp32 error is <= 2^-23 G):
+      first moment   |dm| <= 2^-22 (b1 |m| + (1-b1) G)        (an FMA of two rounded terms; the two
+                                                               terms can cancel, their errors cannot)
+      second moment  |dv| <= 2^-21 (b2 v + (1-b2) G^2)        (all terms are non-negative)
+      parameter      |dp| <= 2 ulp(p) + ADAMW_STEP_RTOL x step + (change of the step when the second
+                     moment moves by its bound), the step evaluated with b1 |m| + (1-b1) G in
+                     place of the new first moment
+    Also returns the squared differences and norms of m and v for list-wide figures."""
+    dev = p_new.device
+    f64 = lambda a: a.detach().reshape(-1).to(torch.float64)
+    up = lambda a: torch.from_numpy(a).to(dev)
+    G = f64(x).abs_().mul_(abs(beta)).add_(f64(y).abs_(), alpha=abs(k))
+    m_unc = f64(m_old).abs_().mul_(beta1).add_(G, alpha=1.0 - beta1)
+    mo_d, vo_d, po_d = up(mo), up(vo), up(po)
+    dm = f64(m_new).sub_(mo_d)
+    excess = float((dm.abs() - m_unc * 2.0 ** -22 - 1e-300).max())
+    assert excess <= 0.0, f"{name}: a first moment is {excess:.3e} beyond its bound"
+    dv = f64(v_new).sub_(vo_d)
+    tol_v = f64(v_old).mul_(beta2).add_(G * G, alpha=1.0 - beta2).mul_(2.0 ** -21)
+    excess = float((dv.abs() - tol_v - 1e-300).max())
+    assert excess <= 0.0, f"{name}: a second moment is {excess:.3e} beyond its bound"
+    # The step lr m^ / (sqrt(v^) + eps): its own roundings (ADAMW_STEP_RTOL), and what the
+    # allowed error of the second moment does to it (where g' nearly cancels and v was ~0, the
+    # new second moment is small and carries the cancellation error of g'^2; evaluated, not
+    # linearised: the step at the smallest second moment the bound allows minus the step at
+    # the oracle's).  Both with the uncancelled first moment.
+    bc1, bc2 = 1.0 - beta1 ** t, 1.0 - beta2 ** t
+    m_unc.mul_(lr / bc1)
+    step_mid = m_unc / vo_d.div(bc2).sqrt_().add_(eps_adam)
+    step_hi = m_unc / vo_d.sub(tol_v).clamp_(min=0.0).div_(bc2).sqrt_().add_(eps_adam)
+    _, e = torch.frexp(p_old.detach().reshape(-1))
+    ulp = torch.ldexp(torch.ones_like(e, dtype=torch.float64), e - 24)
+    tol_p = ulp.mul_(2.0).add_(step_hi, alpha=ADAMW_STEP_RTOL).add_(step_hi - step_mid)
+    over = f64(p_new).sub_(po_d).abs_() - tol_p
+    excess = float(over.max())
+    if excess > 0.0:
+        i = int(over.argmax())
+        at = lambda a: float(a.detach().reshape(-1)[i])
+        raise AssertionError(
+            f"{name}: a parameter is {excess:.3e} beyond its bound at element {i}: p_old={at(p_old)!r} "
+            f"p_new={at(p_new)!r} oracle={po[i]!r} m_old={at(m_old)!r} m_new={at(m_new)!r} oracle_m={mo[i]!r} "
+            f"v_old={at(v_old)!r} v_new={at(v_new)!r} oracle_v={vo[i]!r} g={at(x)!r} d={at(y)!r} tol={float(tol_p[i])!r}")
+    return (float(torch.dot(dm, dm)), float(torch.dot(mo_d, mo_d)),
+            float(torch.dot(dv, dv)), float(torch.dot(vo_d, vo_d)))
