@@ -122,6 +122,7 @@ struct gac_ctx {
 
   double* dev_partials = nullptr;  // 3 doubles per workgroup
   unsigned int* dev_ticket = nullptr;  // arrival counter of the reduction's workgroups (zero between launches)
+  unsigned long long* dev_work = nullptr;  // chunk counter of pass 2 (zeroed by the finalize step)
   double* dev_sums = nullptr;      // 3 doubles
   gac_result* dev_result = nullptr;
   gac_result* pinned_result = nullptr;      // host address of the pinned result record
@@ -328,6 +329,7 @@ DecideParams decide_params(const gac_ctx* ctx) {
   p.hist_cap = ctx->hist_cap;
   p.step_value = 0;
   p.cur = ctx->snapshot ? ctx->dev_cur : nullptr;
+  p.work = ctx->dev_work;
   return p;
 }
 
@@ -368,18 +370,20 @@ int run_step(gac_ctx* ctx, void* const* grad_ptrs, bool do_reduce, const double*
   if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[2], stream));
   if (kind == ApplyKind::kExchange) {
     GAC_HIP(ctx, gac::launch_exchange(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
-                                      ctx->chunk_elems, ctx->dev_result, ctx->grid_apply, stream));
+                                      ctx->chunk_elems, ctx->dev_result, ctx->dev_work, ctx->grid_apply,
+                                      stream));
   } else if (kind == ApplyKind::kPlain && ctx->snapshot) {
     GAC_HIP(ctx, gac::launch_snap_apply(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
-                                        ctx->chunk_elems, ctx->dev_result, ctx->dev_cur,
+                                        ctx->chunk_elems, ctx->dev_result, ctx->dev_work, ctx->dev_cur,
                                         ctx->snap_delta, ctx->grid_apply, stream));
   } else if (kind == ApplyKind::kPlain) {
     GAC_HIP(ctx, gac::launch_apply(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
-                                   ctx->chunk_elems, ctx->dev_result, ctx->grid_apply, stream));
+                                   ctx->chunk_elems, ctx->dev_result, ctx->dev_work, ctx->grid_apply,
+                                   stream));
   } else {
     GAC_HIP(ctx, gac::launch_apply_adamw(ctx->dtype, ctx->dev_segs, ctx->dev_adam, ctx->n_tensors,
-                                         ctx->n_chunks, ctx->chunk_elems, ctx->dev_result, *adam,
-                                         ctx->grid_adamw, stream));
+                                         ctx->n_chunks, ctx->chunk_elems, ctx->dev_result,
+                                         ctx->dev_work, *adam, ctx->grid_adamw, stream));
   }
   if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[3], stream));
   if (host_out != nullptr) return wait_result(ctx, host_out);
@@ -500,15 +504,16 @@ int init_impl(gac_ctx** out, const gac_config* cfg) {
     if (g > gac::kMaxGridBlocks) g = gac::kMaxGridBlocks;
     return static_cast<int>(g);
   };
-  // Default grids (persistent kernels, static striding), from measurements on MI355X: the
-  // reduction does best with one workgroup per CU, the in-place pass with workgroups on
-  // three quarters of the CUs; more requesters lower the achieved HBM bandwidth.
+  // Default grids, from measurements on MI355X: the reduction (static striding, one partial
+  // sum per workgroup) does best with one workgroup per CU, the in-place pass (chunks drawn
+  // from a counter) with workgroups on 13/16 of the CUs; more requesters lower the achieved
+  // HBM bandwidth.
   const int64_t cus = prop.multiProcessorCount;
   ctx->cus = static_cast<int>(cus);
   ctx->apply_blocks_fixed = cfg->apply_blocks > 0;
   ctx->grid = pick_grid(cfg->grid_blocks, cus);
   ctx->grid_state = pick_grid(0, cus * 4);
-  ctx->grid_apply = pick_grid(cfg->apply_blocks, cus * 3 / 4);
+  ctx->grid_apply = pick_grid(cfg->apply_blocks, cus * 13 / 16);
   ctx->grid_adamw = pick_grid(cfg->apply_blocks, cus * gac::adamw_blocks_per_cu(ctx->dtype));
 
   ctx->state.assign(n, nullptr);
@@ -541,6 +546,8 @@ int init_impl(gac_ctx** out, const gac_config* cfg) {
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_partials), sizeof(double) * 3 * ctx->grid));
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_ticket), sizeof(unsigned int)));
   GAC_HIP(ctx, gac::launch_set_word(ctx->dev_ticket, 0u, nullptr));
+  GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_work), sizeof(unsigned long long)));
+  GAC_HIP(ctx, gac::launch_set_step(reinterpret_cast<int64_t*>(ctx->dev_work), 0, nullptr));
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_cur), sizeof(int32_t)));
   GAC_HIP(ctx, gac::launch_set_word(reinterpret_cast<uint32_t*>(ctx->dev_cur), 0u, nullptr));
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_sums), sizeof(double) * 3));
@@ -586,6 +593,7 @@ void gac_destroy(gac_ctx* ctx) {
     if (ctx->state1_alloc) (void)hipFree(ctx->state1_alloc);
     if (ctx->dev_ticket) (void)hipFree(ctx->dev_ticket);
     if (ctx->dev_cur) (void)hipFree(ctx->dev_cur);
+    if (ctx->dev_work) (void)hipFree(ctx->dev_work);
     if (ctx->dev_segs) (void)hipFree(ctx->dev_segs);
     if (ctx->dev_segs_state) (void)hipFree(ctx->dev_segs_state);
     if (ctx->dev_adam) (void)hipFree(ctx->dev_adam);
@@ -776,8 +784,9 @@ int time_probe(gac_ctx* ctx, void* const* grad_ptrs, void* const* state_ptrs, bo
                                       ctx->dev_result, nullptr, decide_params(ctx), /*mode=*/0,
                                       0, stream));
     } else {
+      GAC_HIP(ctx, gac::launch_set_step(reinterpret_cast<int64_t*>(ctx->dev_work), 0, stream));
       GAC_HIP(ctx, gac::launch_apply_probe(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
-                                           ctx->chunk_elems, grid, stream));
+                                           ctx->chunk_elems, ctx->dev_work, grid, stream));
     }
     GAC_HIP(ctx, hipEventRecord(e1, stream));
     GAC_HIP(ctx, hipEventSynchronize(e1));
@@ -916,7 +925,7 @@ int place_state_impl(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidate
   rep->chosen = best;
   // workgroup count of the in-place pass at the chosen location
   if (!ctx->apply_blocks_fixed) {
-    const int64_t tries[3] = {ctx->cus * 3ll / 4, ctx->cus, 2ll * ctx->cus};
+    const int64_t tries[4] = {ctx->cus * 3ll / 4, ctx->cus * 13ll / 16, ctx->cus * 7ll / 8, ctx->cus};
     int n = 0, best_blocks = ctx->grid_apply;
     double best_ms = 0.0;
     for (int64_t b : tries) {
@@ -938,10 +947,6 @@ int place_state_impl(gac_ctx* ctx, void* const* grad_ptrs, int32_t max_candidate
       ++n;
     }
     rep->n_blocks_tried = n;
-    // The probe resolves about half a per cent.  Within that, one workgroup per CU is taken:
-    // full steps on the same tensors ran 0.8 % faster with it whenever the probe was undecided.
-    for (int i = 0; i < n; ++i)
-      if (rep->blocks_tried[i] == ctx->cus && rep->blocks_ms[i] <= 1.006 * best_ms) best_blocks = ctx->cus;
     if (rc == GAC_OK) ctx->grid_apply = best_blocks;
   }
   rep->apply_blocks = ctx->grid_apply;
@@ -1166,7 +1171,7 @@ int static_step_impl(const gac_config* cfg, void* const* grad_ptrs, int64_t step
   // the same defaults as gac_init, so that the partial sums (and with them every bit of the
   // result) are those of gac_step
   const int grid = pick_grid(cfg->grid_blocks, cus, gac::kStaticMaxGrid);
-  const int grid_apply = pick_grid(cfg->apply_blocks, cus * 3 / 4, gac::kMaxGridBlocks);
+  const int grid_apply = pick_grid(cfg->apply_blocks, cus * 13 / 16, gac::kMaxGridBlocks);
 
   // The tensor table goes to the device as kernel arguments, a batch at a time; the first
   // batch also clears the ticket counter (an earlier call that was cut short may have left it
@@ -1210,10 +1215,11 @@ int static_step_impl(const gac_config* cfg, void* const* grad_ptrs, int64_t step
   p.hist_cap = 0;
   p.step_value = step;
   p.cur = nullptr;
+  p.work = sc.work;
   GAC_HIP(nullptr, gac::launch_reduce(cfg->dtype, sc.segs, n_chunks, chunk_elems, sc.partials, sc.ticket,
                                       grid, sc.sums, sc.result, result_out, p, /*mode=*/2, 0, stream));
   GAC_HIP(nullptr, gac::launch_apply(cfg->dtype, sc.segs, n, n_chunks, chunk_elems, sc.result,
-                                     grid_apply, stream));
+                                     sc.work, grid_apply, stream));
   return GAC_OK;
 }
 }  // namespace

@@ -41,6 +41,7 @@ struct DecideParams {
   int64_t step_value;    // used when `step` is null: the number this update gets (the caller counts)
   int32_t* cur;          // snapshot form: which of the two state buffers is current (flipped by a
                          // finite step); null otherwise
+  unsigned long long* work;  // the counter pass 2 draws its chunks from; the finalize step zeroes it
 };
 
 constexpr int kMaxHistory = 4096;  // the statistics kernel sorts the ring in LDS
@@ -81,8 +82,11 @@ hipError_t launch_reduce(int dtype, const Seg* dev_segs, int64_t n_chunks, int c
 hipError_t launch_finalize(const double* sums_in, double* sums_out, gac_result* dev_result,
                            gac_result* host_result, DecideParams p, hipStream_t stream);
 
+// The pass-2 launchers take dev_work, a device counter that must be zero at launch (the
+// finalize step leaves it so): their workgroups draw chunk indices from it.
 hipError_t launch_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
-                        int chunk_elems, const gac_result* dev_result, int grid, hipStream_t stream);
+                        int chunk_elems, const gac_result* dev_result, unsigned long long* dev_work,
+                        int grid, hipStream_t stream);
 
 // Table 3 statistics over ring entries of steps first_step .. last_step (1-based, at most
 // hist_cap of them); writes *dev_out and, if not null, *host_out (host-mapped).
@@ -92,22 +96,24 @@ hipError_t launch_diag(const double* hist_c, const int32_t* hist_regime, int his
 
 // Buffer-exchange pass 2: writes g' over the old state (Seg::b) in the projection regime only.
 hipError_t launch_exchange(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
-                           int chunk_elems, const gac_result* dev_result, int grid,
-                           hipStream_t stream);
+                           int chunk_elems, const gac_result* dev_result,
+                           unsigned long long* dev_work, int grid, hipStream_t stream);
 
 // Pass 2 of the snapshot form: g <- scale_g g + coef_d d_old in place when the step projects or
 // clips, nothing otherwise (the state was already written by pass 1).
 hipError_t launch_snap_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
-                             int chunk_elems, const gac_result* dev_result, int32_t* dev_cur,
-                             int64_t snap_delta, int grid, hipStream_t stream);
+                             int chunk_elems, const gac_result* dev_result,
+                             unsigned long long* dev_work, int32_t* dev_cur, int64_t snap_delta,
+                             int grid, hipStream_t stream);
 
 // The same traffic as the projecting apply pass with every value written back unchanged.
 hipError_t launch_apply_probe(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
-                              int chunk_elems, int grid, hipStream_t stream);
+                              int chunk_elems, unsigned long long* dev_work, int grid,
+                              hipStream_t stream);
 hipError_t launch_apply_adamw(int dtype, const Seg* dev_segs, const AdamSeg* dev_adam,
                               int n_tensors, int64_t n_chunks, int chunk_elems,
-                              const gac_result* dev_result, AdamScalars h, int grid,
-                              hipStream_t stream);
+                              const gac_result* dev_result, unsigned long long* dev_work,
+                              AdamScalars h, int grid, hipStream_t stream);
 
 // Threshold pairs of one sweep, passed to the kernel by value.
 struct SweepPairs {
@@ -132,6 +138,7 @@ constexpr int kStaticMaxTensors = GAC_STATIC_MAX_TENSORS;
 constexpr int kStaticMaxGrid = 1024;  // partial-sum slots
 struct StaticScratch {
   unsigned int* ticket;
+  unsigned long long* work;
   double* sums;
   gac_result* result;
   double* partials;

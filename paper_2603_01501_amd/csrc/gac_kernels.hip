@@ -370,6 +370,7 @@ struct FinalArgs {
 
 // Thread 0 holds the sums.
 __device__ __forceinline__ void finish(const double (&s)[3], const FinalArgs& f) {
+  if (f.p.work != nullptr) *f.p.work = 0ull;  // pass 2 draws its chunks from zero
   if (f.sums_out != nullptr) {
     f.sums_out[0] = s[0];
     f.sums_out[1] = s[1];
@@ -592,30 +593,55 @@ __device__ __forceinline__ void apply_chunk_generic(const Chunk& ch, bool projec
 // reads in flight during the arithmetic and the stores.  Other chunks (tensor tails,
 // non-default chunk sizes) go to `generic`.
 //
+// Which workgroup takes which chunk is decided while the kernel runs: workgroup b starts with
+// chunk b and draws every further one from a device-wide counter (*work, zero at launch; the
+// finalize step resets it).  Pass 2 is element-wise, so the assignment changes no bit of the
+// result, only who is idle at the end: with a static stride the workgroups of half the XCDs
+// finished 0.5-6 % later than the others (measured on MI355X: they see a slower path to
+// memory, and which half depends on the launch shape), and the kernel lasted as long as the
+// slowest.  The index is fetched one chunk ahead by lane 0 and handed to the other lanes
+// through LDS, one barrier per chunk.
+//
 // Chunks are walked from the end of the list towards its start (the reduction pass has just
 // streamed the list front to back, so its last chunks would be the ones still cached).  With
 // the non-temporal loads of pass 1 this measured no different from a forward walk on 2-3 GB
 // lists; it is kept because it costs nothing.
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(static_cast<uint64_t>(v) >> 32));
+  return static_cast<int64_t>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
 template <int DT, int T, int U, typename Tile, typename Load, typename Store, typename Generic>
 __device__ __forceinline__ void walk_tiles(const Seg* __restrict__ segs, int n_tensors,
-                                           int64_t n_chunks, int chunk_elems, Load load_tile,
+                                           int64_t n_chunks, int chunk_elems,
+                                           unsigned long long* __restrict__ work, Load load_tile,
                                            Store store_tile, Generic generic) {
   constexpr int N = Elem<DT>::kPerVec;
+  __shared__ unsigned long long drawn[2];
   auto whole = [&](const Chunk& ch) { return ch.len == T * U * N; };
+  // lane 0 draws the next index into drawn[slot]; the others read it after the next barrier
+  auto draw = [&](int slot) {
+    if (threadIdx.x == 0) drawn[slot] = gridDim.x + atomicAdd(work, 1ull);
+  };
   int t = n_tensors - 1;
   int64_t cr = blockIdx.x;
   if (cr >= n_chunks) return;
+  draw(0);
   Chunk cur = locate<true>(segs, t, n_chunks - 1 - cr, chunk_elems, Elem<DT>::kSize);
   bool cur_whole = whole(cur);
   Tile tc = {};
   if (cur_whole) load_tile(cur, tc);
+  __syncthreads();
+  cr = uniform64(static_cast<int64_t>(drawn[0]));
+  int slot = 1;
   for (;;) {
-    cr += gridDim.x;
     const bool more = cr < n_chunks;
     Chunk next = cur;
     bool next_whole = false;
     Tile tn = {};
     if (more) {
+      draw(slot);  // the index after this one: its latency hides behind this tile's traffic
       next = locate<true>(segs, t, n_chunks - 1 - cr, chunk_elems, Elem<DT>::kSize);
       next_whole = whole(next);
       if (next_whole) load_tile(next, tn);
@@ -626,6 +652,9 @@ __device__ __forceinline__ void walk_tiles(const Seg* __restrict__ segs, int n_t
       generic(cur);
     }
     if (!more) break;
+    __syncthreads();
+    cr = uniform64(static_cast<int64_t>(drawn[slot]));
+    slot ^= 1;
     cur = next;
     cur_whole = next_whole;
     tc = tn;
@@ -648,6 +677,7 @@ __global__ __launch_bounds__(T) void apply_kernel(const Seg* __restrict__ segs,
                                                          int n_tensors, int64_t n_chunks,
                                                          int chunk_elems,
                                                          const gac_result* __restrict__ res,
+                                                         unsigned long long* __restrict__ work,
                                                          float probe_k, float probe_beta) {
   if (!PROBE && res->nonfinite) return;  // convention: a non-finite step modifies nothing
   // g <- scale_g * g + coef_d * d when the step projects and/or clips, else g stays
@@ -683,7 +713,7 @@ __global__ __launch_bounds__(T) void apply_kernel(const Seg* __restrict__ segs,
     }
   };
 
-  walk_tiles<DT, T, U, Tile>(segs, n_tensors, n_chunks, chunk_elems, load_tile, store_tile,
+  walk_tiles<DT, T, U, Tile>(segs, n_tensors, n_chunks, chunk_elems, work, load_tile, store_tile,
                              [&](const Chunk& ch) { apply_chunk_generic<DT, T, U, PROBE>(ch, project, k, beta); });
 }
 
@@ -695,7 +725,8 @@ template <int DT, int T, int U>
 __global__ __launch_bounds__(T) void exchange_kernel(const Seg* __restrict__ segs,
                                                             int n_tensors, int64_t n_chunks,
                                                             int chunk_elems,
-                                                            const gac_result* __restrict__ res) {
+                                                            const gac_result* __restrict__ res,
+                                                            unsigned long long* __restrict__ work) {
   constexpr int N = Elem<DT>::kPerVec;
   if (res->nonfinite || !res->modified) return;
   const float k = static_cast<float>(res->coef_d);
@@ -728,7 +759,7 @@ __global__ __launch_bounds__(T) void exchange_kernel(const Seg* __restrict__ seg
       store_elem<DT>(ch.b, i, fmaf(k, load_elem<DT>(ch.b, i), beta * load_elem<DT>(ch.a, i)));
   };
 
-  walk_tiles<DT, T, U, Tile>(segs, n_tensors, n_chunks, chunk_elems, load_tile, store_tile, generic);
+  walk_tiles<DT, T, U, Tile>(segs, n_tensors, n_chunks, chunk_elems, work, load_tile, store_tile, generic);
 }
 
 // Pass 2 of the snapshot form.  Pass 1 has already stored the raw gradient as the next
@@ -740,6 +771,7 @@ __global__ __launch_bounds__(T) void snap_apply_kernel(const Seg* __restrict__ s
                                                               int n_tensors, int64_t n_chunks,
                                                               int chunk_elems,
                                                               const gac_result* __restrict__ res,
+                                                              unsigned long long* __restrict__ work,
                                                               SnapArgs snap) {
   constexpr int N = Elem<DT>::kPerVec;
   if (res->nonfinite || !res->modified) return;
@@ -775,7 +807,7 @@ __global__ __launch_bounds__(T) void snap_apply_kernel(const Seg* __restrict__ s
       store_elem<DT>(ga, i, fmaf(k, load_elem<DT>(ch.b + old_off, i), beta * load_elem<DT>(ch.a, i)));
   };
 
-  walk_tiles<DT, T, U, Tile>(segs, n_tensors, n_chunks, chunk_elems, load_tile, store_tile, generic);
+  walk_tiles<DT, T, U, Tile>(segs, n_tensors, n_chunks, chunk_elems, work, load_tile, store_tile, generic);
 }
 
 // ------------------------------------------------------------------ pass 2 fused with AdamW
@@ -912,7 +944,8 @@ __device__ __forceinline__ void adamw_quads(const gchar* ga, gchar* gb, gfloat* 
 template <int DT, int T>
 __global__ __launch_bounds__(T) void apply_adamw_kernel(
     const Seg* __restrict__ segs, const AdamSeg* __restrict__ adam, int n_tensors,
-    int64_t n_chunks, int chunk_elems, const gac_result* __restrict__ res, AdamScalars h) {
+    int64_t n_chunks, int chunk_elems, const gac_result* __restrict__ res,
+    unsigned long long* __restrict__ work, AdamScalars h) {
   constexpr int Q = GAC_ADAMW_QUADS;
   if (res->nonfinite) return;
   const int regime = res->regime;
@@ -922,7 +955,11 @@ __global__ __launch_bounds__(T) void apply_adamw_kernel(
   const float beta = static_cast<float>(res->scale_g);
   const int tid = threadIdx.x;
   int t = n_tensors - 1;
-  for (int64_t cr = blockIdx.x; cr < n_chunks; cr += gridDim.x) {
+  // chunks are drawn from a device-wide counter, one ahead (see walk_tiles)
+  __shared__ unsigned long long drawn[2];
+  int slot = 0;
+  for (int64_t cr = blockIdx.x; cr < n_chunks; slot ^= 1) {
+    if (tid == 0) drawn[slot] = gridDim.x + atomicAdd(work, 1ull);
     const Chunk ch = locate<true>(segs, t, n_chunks - 1 - cr, chunk_elems, Elem<DT>::kSize);
     const AdamSeg as = adam[ch.tensor];
     gfloat* pp = (gfloat*)(as.p) + ch.elem_off;
@@ -949,6 +986,8 @@ __global__ __launch_bounds__(T) void apply_adamw_kernel(
       }
       copy_elem<DT>(ch.a, ch.b, i);
     }
+    __syncthreads();
+    cr = uniform64(static_cast<int64_t>(drawn[slot]));
   }
 }
 
@@ -1151,67 +1190,69 @@ hipError_t launch_finalize(const double* sums_in, double* sums_out, gac_result* 
 }
 
 hipError_t launch_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
-                        int chunk_elems, const gac_result* dev_result, int grid,
-                        hipStream_t stream) {
+                        int chunk_elems, const gac_result* dev_result, unsigned long long* dev_work,
+                        int grid, hipStream_t stream) {
   if (dtype == GAC_F32) {
     apply_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL, false><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, 0.0f, 1.0f);
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, dev_work, 0.0f, 1.0f);
   } else {
     apply_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL, false><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, 0.0f, 1.0f);
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, dev_work, 0.0f, 1.0f);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_apply_probe(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
-                              int chunk_elems, int grid, hipStream_t stream) {
+                              int chunk_elems, unsigned long long* dev_work, int grid,
+                              hipStream_t stream) {
   if (dtype == GAC_F32) {
     apply_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL, true><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, nullptr, 0.0f, 1.0f);
+        dev_segs, n_tensors, n_chunks, chunk_elems, nullptr, dev_work, 0.0f, 1.0f);
   } else {
     apply_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL, true><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, nullptr, 0.0f, 1.0f);
+        dev_segs, n_tensors, n_chunks, chunk_elems, nullptr, dev_work, 0.0f, 1.0f);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_exchange(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
-                           int chunk_elems, const gac_result* dev_result, int grid,
-                           hipStream_t stream) {
+                           int chunk_elems, const gac_result* dev_result,
+                           unsigned long long* dev_work, int grid, hipStream_t stream) {
   if (dtype == GAC_F32) {
     exchange_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result);
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, dev_work);
   } else {
     exchange_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result);
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, dev_work);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_snap_apply(int dtype, const Seg* dev_segs, int n_tensors, int64_t n_chunks,
-                             int chunk_elems, const gac_result* dev_result, int32_t* dev_cur,
-                             int64_t snap_delta, int grid, hipStream_t stream) {
+                             int chunk_elems, const gac_result* dev_result,
+                             unsigned long long* dev_work, int32_t* dev_cur, int64_t snap_delta,
+                             int grid, hipStream_t stream) {
   const SnapArgs sn = {dev_cur, snap_delta};
   if (dtype == GAC_F32) {
     snap_apply_kernel<GAC_F32, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, sn);
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, dev_work, sn);
   } else {
     snap_apply_kernel<GAC_BF16, GAC_APPLY_THREADS, GAC_APPLY_UNROLL><<<grid, GAC_APPLY_THREADS, 0, stream>>>(
-        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, sn);
+        dev_segs, n_tensors, n_chunks, chunk_elems, dev_result, dev_work, sn);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_apply_adamw(int dtype, const Seg* dev_segs, const AdamSeg* dev_adam,
                               int n_tensors, int64_t n_chunks, int chunk_elems,
-                              const gac_result* dev_result, AdamScalars h, int grid,
-                              hipStream_t stream) {
+                              const gac_result* dev_result, unsigned long long* dev_work,
+                              AdamScalars h, int grid, hipStream_t stream) {
   if (dtype == GAC_F32) {
     apply_adamw_kernel<GAC_F32, GAC_ADAMW_THREADS><<<grid, GAC_ADAMW_THREADS, 0, stream>>>(
-        dev_segs, dev_adam, n_tensors, n_chunks, chunk_elems, dev_result, h);
+        dev_segs, dev_adam, n_tensors, n_chunks, chunk_elems, dev_result, dev_work, h);
   } else {
     apply_adamw_kernel<GAC_BF16, GAC_ADAMW_THREADS><<<grid, GAC_ADAMW_THREADS, 0, stream>>>(
-        dev_segs, dev_adam, n_tensors, n_chunks, chunk_elems, dev_result, h);
+        dev_segs, dev_adam, n_tensors, n_chunks, chunk_elems, dev_result, dev_work, h);
   }
   return hipGetLastError();
 }
@@ -1273,6 +1314,7 @@ hipError_t launch_fill_segs(Seg* dev_table, const SegBatch& batch, unsigned int*
 // kernels can use is looked up once per device and kept in g_scratch_ptr.
 namespace {
 constexpr size_t kScratchTicketOff = 0;
+constexpr size_t kScratchWorkOff = 8;
 constexpr size_t kScratchSumsOff = 64;
 constexpr size_t kScratchResultOff = 128;
 constexpr size_t kScratchPartialsOff = 256;
@@ -1308,6 +1350,7 @@ hipError_t static_scratch(int device, StaticScratch* out) {
   }
   unsigned char* b = static_cast<unsigned char*>(base);
   out->ticket = reinterpret_cast<unsigned int*>(b + kScratchTicketOff);
+  out->work = reinterpret_cast<unsigned long long*>(b + kScratchWorkOff);
   out->sums = reinterpret_cast<double*>(b + kScratchSumsOff);
   out->result = reinterpret_cast<gac_result*>(b + kScratchResultOff);
   out->partials = reinterpret_cast<double*>(b + kScratchPartialsOff);

@@ -33,12 +33,12 @@ int adamw_blocks_per_cu(int) { return 1; }
 hipError_t launch_reduce(int, const Seg*, int64_t, int, double*, unsigned int*, int, double*, gac_result*,
                          gac_result*, DecideParams, int, int64_t, hipStream_t) { return reached("reduce"); }
 hipError_t launch_finalize(const double*, double*, gac_result*, gac_result*, DecideParams, hipStream_t) { return reached("finalize"); }
-hipError_t launch_apply(int, const Seg*, int, int64_t, int, const gac_result*, int, hipStream_t) { return reached("apply"); }
+hipError_t launch_apply(int, const Seg*, int, int64_t, int, const gac_result*, unsigned long long*, int, hipStream_t) { return reached("apply"); }
 hipError_t launch_diag(const double*, const int32_t*, int, int64_t, int64_t, double, gac_diag*, gac_diag*, hipStream_t) { return reached("diag"); }
-hipError_t launch_exchange(int, const Seg*, int, int64_t, int, const gac_result*, int, hipStream_t) { return reached("exchange"); }
-hipError_t launch_snap_apply(int, const Seg*, int, int64_t, int, const gac_result*, int32_t*, int64_t, int, hipStream_t) { return reached("snap_apply"); }
-hipError_t launch_apply_probe(int, const Seg*, int, int64_t, int, int, hipStream_t) { return reached("apply_probe"); }
-hipError_t launch_apply_adamw(int, const Seg*, const AdamSeg*, int, int64_t, int, const gac_result*, AdamScalars, int, hipStream_t) { return reached("apply_adamw"); }
+hipError_t launch_exchange(int, const Seg*, int, int64_t, int, const gac_result*, unsigned long long*, int, hipStream_t) { return reached("exchange"); }
+hipError_t launch_snap_apply(int, const Seg*, int, int64_t, int, const gac_result*, unsigned long long*, int32_t*, int64_t, int, hipStream_t) { return reached("snap_apply"); }
+hipError_t launch_apply_probe(int, const Seg*, int, int64_t, int, unsigned long long*, int, hipStream_t) { return reached("apply_probe"); }
+hipError_t launch_apply_adamw(int, const Seg*, const AdamSeg*, int, int64_t, int, const gac_result*, unsigned long long*, AdamScalars, int, hipStream_t) { return reached("apply_adamw"); }
 hipError_t launch_sweep(const double*, const int32_t*, int, int64_t, int64_t, const SweepPairs&, int, int32_t*, hipStream_t) { return reached("sweep"); }
 hipError_t launch_set_step(int64_t*, int64_t, hipStream_t) { return reached("set_step"); }
 hipError_t launch_set_word(uint32_t*, uint32_t, hipStream_t) { return reached("set_word"); }
