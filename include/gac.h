@@ -172,7 +172,7 @@ void gac_destroy(gac_ctx* ctx);
  *              (pass 2 may still be running) and fills *host_out; the caller skips its
  *              optimizer step if regime is GAC_SKIP.
  * With host_out == NULL and the same pointers as in the previous call, the call only launches
- * kernels (no copy, no host wait, no memset), so it can be captured into a HIP graph and
+ * its two kernels (no copy, no host wait, no memset), so it can be captured into a HIP graph and
  * replayed: the step counter and the record of c_t live on the device and keep counting.
  * Thresholds and max_grad_norm are launch arguments and are frozen into a captured graph.
  * The state d becomes the raw g in all three regimes.  If a sum is not finite (a
@@ -265,19 +265,21 @@ int gac_reset(gac_ctx* ctx, void* hip_stream);
 
 /* State placement (for callers that let the library allocate the state; the paper does not
  * cover where buffers live).  Where the reference state sits in HBM relative to the gradients
- * changes the speed of the in-place pass: measured on MI355X, about 10 % between two buffers
- * in the same third of the physical memory and two buffers in different thirds, while a
- * read-only pass moves a few per cent the other way.  Physical placement cannot be requested,
- * only observed, so this call measures.  It times the reduction pass and a data-preserving
- * probe of the in-place pass (the same loads, arithmetic and stores; every value is written
- * back unchanged) with the state where it is and with up to max_candidates - 1 further
- * allocations of the same size.  These are held until the end, with spacer allocations
- * between them when the state is smaller than 12 GiB, so that each lands at least 12 GiB
- * deeper in memory than the one before.  The search ends early once a location 3 % better
- * than the first has been followed by two that are no better, or after eight in a row
- * without gain.  The state is then moved (contents preserved bit for bit) to the location
- * with the smallest sum of the two times, everything else is freed, and the workgroup count
- * of the in-place pass is picked the same way (unless gac_config.apply_blocks fixed it).
+ * changes the speed of both passes a little, in opposite directions: measured on MI355X, two
+ * buffers in different thirds of the physical memory run the in-place pass ~3 % faster and the
+ * read-only pass ~4 % slower than two buffers in the same third, so the whole step moves by
+ * under 1 % (it was ~10 % before pass 2 drew its chunks in order).  Physical placement
+ * cannot be requested, only observed, so this call measures.  It times the reduction pass and
+ * a data-preserving probe of the in-place pass (the same loads, arithmetic and stores; every
+ * value is written back unchanged) with the state where it is and with up to
+ * max_candidates - 1 further allocations of the same size.  These are held until the end
+ * (report->bytes_held_peak), with spacer allocations between them when the state is smaller
+ * than 12 GiB, so that each lands at least 12 GiB deeper in memory than the one before.  The
+ * search ends early once a location 3 % better than the first has been followed by two that
+ * are no better, or after eight in a row without gain.  The state is then moved (contents
+ * preserved bit for bit) to the location with the smallest sum of the two times if that is at
+ * least 1 % better than where it was, everything else is freed, and the workgroup count of the
+ * in-place pass is picked the same way (unless gac_config.apply_blocks fixed it).
  *   grad_ptrs        the gradient buffers the steps will use (contents preserved bit for bit;
  *                    nothing else may touch them during the call)
  *   max_candidates   1 .. GAC_MAX_PLACEMENT_CANDIDATES; 1 only tunes the workgroup count

@@ -2,21 +2,27 @@
 //
 // The step is two streaming passes over the gradient list g and the reference state d:
 //   pass 1 (reduce_kernel)   three inner products <g,d>, <g,g>, <d,d>      (Appendix A.1)
-//   finalize_kernel          cosine with eps, regime, alpha, coefficient    (Eq. 1, Sec. 4.2)
+//     its last workgroup     cosine with eps, regime, alpha, coefficient    (Eq. 1, Sec. 4.2)
 //   pass 2 (apply_kernel)    g <- beta g + k d in place and d <- raw g      (Eq. 4, App. A.2)
 //          (apply_adamw_kernel: the same with AdamW consuming g' in registers, Table 2;
-//           exchange_kernel: g' written over the old state, for callers that swap buffers)
-// Beside them: state_kernel (zero / copy of the state), diag_kernel and sweep_kernel (the
-// statistics of Table 3 and regime counts under other thresholds over the recorded c_t).
+//           exchange_kernel: g' written over the old state, for callers that swap buffers;
+//           snap_apply_kernel: g' alone, when pass 1 has already written the snapshot)
+// Beside them: finalize_kernel (the scalar step alone, for sums that come from other ranks),
+// state_kernel (zero / copy of the state), diag_kernel and sweep_kernel (the statistics of
+// Table 3 and regime counts under other thresholds over the recorded c_t).
 // Both passes are bound by HBM bandwidth (3 FMA per 2 loaded elements, 1 FMA per 4 moved
 // elements), so there is no matrix-core work here; what matters is 16-byte accesses that
-// coalesce to full cache lines, many loads in flight per wave, and all CUs busy.
+// coalesce to full cache lines, many loads in flight per wave, all CUs busy to the end, and
+// workgroups that work on neighbouring parts of memory at the same time.
 //
-// Work distribution: the tensor list is cut into chunks (gac_internal.h: Seg); workgroup b
-// of a G-wide persistent grid takes chunks b, b+G, b+2G, ...  The chunk -> workgroup map is
-// static, every workgroup writes its own partial sums, and the finalize kernel adds them in
-// a fixed order (lane j takes partials j, j+256, ...; then a fixed tree over lanes and
-// waves), so results are bit-reproducible.  No floating-point atomics anywhere.
+// Work distribution: the tensor list is cut into chunks (gac_internal.h: Seg).
+// Pass 1: workgroup b of a G-wide persistent grid takes chunks b, b+G, b+2G, ...  The
+// chunk -> workgroup map is static, every workgroup writes its own partial sums, and the last
+// workgroup to finish adds them in a fixed order (lane j takes partials j, j+256, ...; then a
+// fixed tree over lanes and waves), so results are bit-reproducible.  No floating-point
+// atomics anywhere.
+// Pass 2 is element-wise, so any assignment gives the same bits: its workgroups draw chunk
+// indices in order from a device-wide counter (walk_tiles).
 //
 // Accumulation: products are formed and summed in fp32 over one group of at most
 // GAC_REDUCE_UNROLL * 8 elements per lane (for bf16 inputs each product is exact in fp32), then the
@@ -56,13 +62,14 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // Both passes saturate HBM with FEW workgroups that each keep many 16-byte accesses in
 // flight; more resident waves only add contention at the memory controllers.
 // Pass 1 is a pure read stream: one 256-thread workgroup per CU, 8 x 16 B loads per array
-// in flight per lane, non-temporal loads (7.2 TB/s; 6.7 with six workgroups per CU).
+// in flight per lane, non-temporal loads (7.0-7.2 TB/s; 6.7 with six workgroups per CU; 16 or
+// 32 loads per array in flight are 1-2 % slower).  Its snapshot form also stores: there 16
+// loads per array in flight (GAC_SNAP_DEPTH = 2 groups) are 4-7 % faster than 8.
 // Pass 2 reads and writes the same lines: 512-thread workgroups that load a whole 64 KiB
-// chunk of each array and then store it (8 vectors per lane), on 3/4 of the CUs or on all of
-// them (gac_place_state measures which), non-temporal loads and stores.  Where the two
-// arrays sit in HBM matters more than any of this: 5.4 TB/s with g and d in the same third of
-// the physical memory, 6.2-6.3 TB/s in different thirds (1024 x 4 tiles: 1.5 % slower there,
-// 1 % faster in the same third; 256-thread workgroups: 5.0).
+// chunk of each array and then store it (8 vectors per lane), on 13/16 of the CUs (3/4 to
+// 7/8 measure within 1 %, all CUs 1.3 % slower, 5/8 4 % slower), non-temporal loads and
+// stores; 256 x 16 and 1024 x 4 tiles are within 2 % of 512 x 8.  The cache policy of the
+// stores (plain, nt, sc1, sc0 sc1 and combinations) changes a write stream by under 2 %.
 #ifndef GAC_REDUCE_THREADS
 #define GAC_REDUCE_THREADS 256
 #endif
