@@ -51,7 +51,11 @@ def test_clipping_folded_into_the_step(dtype, rho, c_high, regime, clip_at):
     assert clipped == (clip_at < 1.0 and regime != B.SKIP)
     assert res.modified == int(regime == B.PROJECT or clipped)
     if res.modified:
+        # what pass 2 computes is scale (g + k d): every element and every tensor against the oracle
+        k0 = (dec.alpha - 1.0) * s[0] / s[2] if dec.regime == O.PROJECT else 0.0
         assert U.rel_l2(g, outs) <= U.GRAD_TOL[U.code(dtype)]
+        for j in range(len(SHAPES)):
+            U.check_projected_tensor(g[j], outs[j], g_raw[j], d0[j], scale * k0, scale, U.code(dtype), f"tensor {j}")
     else:
         assert all(U.bits_equal(a, b) for a, b in zip(g, g_raw))
     # the reference state keeps the raw, unclipped gradient
@@ -75,6 +79,9 @@ def test_clipping_in_the_exchange_form_and_fused_adamw():
         torch.cuda.synchronize()
         assert res.regime == regime and res.modified == 1 and res.clip_coef == pytest.approx(scale, rel=1e-6)
         assert U.rel_l2(returned, outs) <= U.GRAD_TOL[B.BF16]
+        k0 = (dec.alpha - 1.0) * s[0] / s[2] if dec.regime == O.PROJECT else 0.0
+        for j in range(len(SHAPES)):
+            U.check_projected_tensor(returned[j], outs[j], g[j], d0[j], scale * k0, scale, B.BF16, f"tensor {j}")
         assert all(U.bits_equal(a, b) for a, b in zip(mine, g))
         # fused AdamW consumes the clipped gradient
         gen = torch.Generator(device=DEV)

@@ -89,7 +89,8 @@ def test_resumed_run_reproduces_the_uninterrupted_one(dtype, caller_state):
     for t in range(k + 1, k + more + 1):
         g = stream.next()
         g_raw = U.clone_list(g)
-        outs, _, dec = O.step(U.host_copies(g), d_oracle, dt, C_LOW, 0.9, EPS)
+        d_before = [W.from_bits(a, dtype).to(DEV) for a in d_oracle]
+        outs, sums, dec = O.step(U.host_copies(g), d_oracle, dt, C_LOW, 0.9, EPS)
         want_c.append(dec.c)
         g_twin = U.clone_list(g)
         r1 = twin.gac_step(g_twin)
@@ -99,7 +100,7 @@ def test_resumed_run_reproduces_the_uninterrupted_one(dtype, caller_state):
         assert r2.step == t and r2.regime == dec.regime == B.PROJECT
         assert abs(r2.c - dec.c) <= U.COS_TOL
         assert all(U.bits_equal(a, b) for a, b in zip(g, g_twin)), "projected gradients differ"
-        assert U.rel_l2(g, outs) <= U.GRAD_TOL[dt]
+        U.check_projected_list(g, outs, g_raw, d_before, sums, dec.alpha, 1.0, dt)
         s1, n1 = exported(twin, dtype)
         s2, n2 = exported(resumed, dtype)
         assert n1 == n2 == t
