@@ -76,8 +76,11 @@ enum {
  * reference state.  A step that neither projects nor clips then has no second pass: 3 N s
  * bytes instead of 4 N s.  A projecting step reads g and the old state and rewrites g
  * (3 N s + 3 N s, two mixed passes instead of one pure read pass and one mixed pass, so it
- * is slower than the default form).  Results are bit-identical to the default form in every
- * regime.  Costs N s bytes of device memory.  Needs a library-allocated state (state_ptrs =
+ * is slower than the default form).  Pass 1 of this form draws its chunks in order (which a
+ * pass that also writes needs to be fast) and therefore keeps one partial sum per chunk,
+ * combined in a fixed order: its results are the same bit for bit on every run and for every
+ * grid_blocks, and equal to the default form's up to the rounding of the partial sums (the
+ * two forms group the same products differently: ~1e-10 relative on the sums).  Costs N s bytes of device memory plus 24 bytes per chunk.  Needs a library-allocated state (state_ptrs =
  * NULL); works with gac_step and gac_reduce_local / gac_apply; gac_step_adamw and
  * gac_place_state return GAC_ERR_UNIMPLEMENTED on such a context. */
 

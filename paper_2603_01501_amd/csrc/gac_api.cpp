@@ -103,6 +103,9 @@ struct gac_ctx {
   std::vector<void*> state1;
   int64_t snap_delta = 0;
   int32_t* dev_cur = nullptr;
+  gac::SnapBuffers snap_buf = {};  // working memory of its pass 1 (one allocation: snap_alloc)
+  void* snap_alloc = nullptr;
+  int grid_snap = 1;
 
   // pointer tables
   Seg* dev_segs = nullptr;        // (gradient, state) per tensor: the table the step kernels read
@@ -341,6 +344,20 @@ int state_op(gac_ctx* ctx, int op, const void* const* src, void* const* dst, hip
   return GAC_OK;
 }
 
+// Pass 1 of whichever form the context has.
+int launch_pass1(gac_ctx* ctx, double* sums_out, gac_result* host_res, int mode, hipStream_t stream) {
+  if (ctx->snapshot) {
+    GAC_HIP(ctx, gac::launch_snap_reduce(ctx->dtype, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
+                                         ctx->snap_buf, ctx->grid_snap, sums_out, ctx->dev_result,
+                                         host_res, decide_params(ctx), mode, ctx->snap_delta, stream));
+  } else {
+    GAC_HIP(ctx, gac::launch_reduce(ctx->dtype, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
+                                    ctx->dev_partials, ctx->dev_ticket, ctx->grid, sums_out,
+                                    ctx->dev_result, host_res, decide_params(ctx), mode, stream));
+  }
+  return GAC_OK;
+}
+
 // Steps shared by gac_step / gac_apply / gac_step_adamw / gac_step_exchange.
 enum class ApplyKind { kPlain, kAdamW, kExchange };
 
@@ -353,10 +370,8 @@ int run_step(gac_ctx* ctx, void* const* grad_ptrs, bool do_reduce, const double*
   gac_result* host_res = host_out ? ctx->pinned_result_dev : nullptr;
   if (do_reduce) {
     // the last workgroup of the reduction to finish also decides the regime
-    GAC_HIP(ctx, gac::launch_reduce(ctx->dtype, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
-                                    ctx->dev_partials, ctx->dev_ticket, ctx->grid, ctx->dev_sums,
-                                    ctx->dev_result, host_res, decide_params(ctx), /*mode=*/2,
-                                    ctx->snap_delta, stream));
+    rc = launch_pass1(ctx, ctx->dev_sums, host_res, /*mode=*/2, stream);
+    if (rc != GAC_OK) return rc;
     if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[1], stream));
   } else {
     if (ev) GAC_HIP(ctx, hipEventRecord(ev->e[1], stream));
@@ -550,6 +565,22 @@ int init_impl(gac_ctx** out, const gac_config* cfg) {
   GAC_HIP(ctx, gac::launch_set_step(reinterpret_cast<int64_t*>(ctx->dev_work), 0, nullptr));
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_cur), sizeof(int32_t)));
   GAC_HIP(ctx, gac::launch_set_word(reinterpret_cast<uint32_t*>(ctx->dev_cur), 0u, nullptr));
+  if (ctx->snapshot) {
+    // working memory of the snapshot form's pass 1, in one allocation:
+    // [chunk sums | group sums | ticket word | chunk counter]
+    const int64_t n_groups = gac::snap_group_count(ctx->n_chunks);
+    const size_t chunk_bytes = sizeof(double) * 3 * static_cast<size_t>(ctx->n_chunks > 0 ? ctx->n_chunks : 1);
+    const size_t group_bytes = sizeof(double) * 3 * static_cast<size_t>(n_groups > 0 ? n_groups : 1);
+    const size_t total = chunk_bytes + group_bytes + 16;
+    GAC_HIP(ctx, hipMalloc(&ctx->snap_alloc, total));
+    GAC_HIP(ctx, hipMemset(ctx->snap_alloc, 0, total));  // set-up: the counters start at zero
+    char* base = static_cast<char*>(ctx->snap_alloc);
+    ctx->snap_buf.chunk_sums = reinterpret_cast<double*>(base);
+    ctx->snap_buf.group_sums = reinterpret_cast<double*>(base + chunk_bytes);
+    ctx->snap_buf.ticket = reinterpret_cast<unsigned int*>(base + chunk_bytes + group_bytes);
+    ctx->snap_buf.draw = reinterpret_cast<unsigned long long*>(base + chunk_bytes + group_bytes + 8);
+    ctx->grid_snap = pick_grid(cfg->grid_blocks, cus);
+  }
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_sums), sizeof(double) * 3));
   GAC_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->dev_result), sizeof(gac_result)));
   GAC_HIP(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned_result), sizeof(gac_result),
@@ -591,6 +622,7 @@ void gac_destroy(gac_ctx* ctx) {
     (void)hipDeviceSynchronize();
     if (ctx->state_alloc) (void)hipFree(ctx->state_alloc);
     if (ctx->state1_alloc) (void)hipFree(ctx->state1_alloc);
+    if (ctx->snap_alloc) (void)hipFree(ctx->snap_alloc);
     if (ctx->dev_ticket) (void)hipFree(ctx->dev_ticket);
     if (ctx->dev_cur) (void)hipFree(ctx->dev_cur);
     if (ctx->dev_work) (void)hipFree(ctx->dev_work);
@@ -655,10 +687,8 @@ int gac_reduce_local(gac_ctx* ctx, void* const* grad_ptrs, void* hip_stream, dou
   rc = upload_segs(ctx, const_cast<const void* const*>(grad_ptrs), ctx->state.data(), stream);
   if (rc != GAC_OK) return rc;
   // sums only: the regime is decided in phase 2, on the global sums
-  GAC_HIP(ctx, gac::launch_reduce(ctx->dtype, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
-                                  ctx->dev_partials, ctx->dev_ticket, ctx->grid, dev_sums3,
-                                  ctx->dev_result, nullptr, decide_params(ctx), /*mode=*/0,
-                                  ctx->snap_delta, stream));
+  rc = launch_pass1(ctx, dev_sums3, nullptr, /*mode=*/0, stream);
+  if (rc != GAC_OK) return rc;
   return GAC_OK;
 }
 
@@ -782,7 +812,7 @@ int time_probe(gac_ctx* ctx, void* const* grad_ptrs, void* const* state_ptrs, bo
       GAC_HIP(ctx, gac::launch_reduce(ctx->dtype, ctx->dev_segs, ctx->n_chunks, ctx->chunk_elems,
                                       ctx->dev_partials, ctx->dev_ticket, ctx->grid, ctx->dev_sums,
                                       ctx->dev_result, nullptr, decide_params(ctx), /*mode=*/0,
-                                      0, stream));
+                                      stream));
     } else {
       GAC_HIP(ctx, gac::launch_set_step(reinterpret_cast<int64_t*>(ctx->dev_work), 0, stream));
       GAC_HIP(ctx, gac::launch_apply_probe(ctx->dtype, ctx->dev_segs, ctx->n_tensors, ctx->n_chunks,
@@ -1217,7 +1247,7 @@ int static_step_impl(const gac_config* cfg, void* const* grad_ptrs, int64_t step
   p.cur = nullptr;
   p.work = sc.work;
   GAC_HIP(nullptr, gac::launch_reduce(cfg->dtype, sc.segs, n_chunks, chunk_elems, sc.partials, sc.ticket,
-                                      grid, sc.sums, sc.result, result_out, p, /*mode=*/2, 0, stream));
+                                      grid, sc.sums, sc.result, result_out, p, /*mode=*/2, stream));
   GAC_HIP(nullptr, gac::launch_apply(cfg->dtype, sc.segs, n, n_chunks, chunk_elems, sc.result,
                                      sc.work, grid_apply, stream));
   return GAC_OK;

@@ -70,12 +70,28 @@ int adamw_blocks_per_cu(int dtype);
 // Pass 1 with the finalize step folded into its last-arriving workgroup.  The sums go to
 // sums_out (if not null).  mode bit 1: decide and write the result record to dev_result and,
 // if not null, also to host_result (host-mapped pinned memory).  dev_ticket is one zero
-// word that the kernel leaves at zero.  With p.cur set (snapshot form) the raw gradient is
-// also written to the state buffer that is not current, snap_delta bytes from the other.
+// word that the kernel leaves at zero.
 hipError_t launch_reduce(int dtype, const Seg* dev_segs, int64_t n_chunks, int chunk_elems,
                          double* dev_partials, unsigned int* dev_ticket, int grid, double* sums_out,
                          gac_result* dev_result, gac_result* host_result, DecideParams p, int mode,
-                         int64_t snap_delta, hipStream_t stream);
+                         hipStream_t stream);
+
+// Pass 1 of the snapshot form (p.cur set), two launches: the streaming kernel (the sums per
+// chunk, and the raw gradient written to the state buffer that is not current, snap_delta bytes
+// from the other) and a small kernel that adds the chunk sums in a fixed order and does the
+// finalize step.  Working memory: a chunk counter and a ticket word (zero at launch, left at
+// zero), 3 doubles per chunk, 3 doubles per group of chunks (snap_group_count of them).
+struct SnapBuffers {
+  unsigned long long* draw;
+  double* chunk_sums;
+  double* group_sums;
+  unsigned int* ticket;
+};
+int64_t snap_group_count(int64_t n_chunks);
+hipError_t launch_snap_reduce(int dtype, const Seg* dev_segs, int64_t n_chunks, int chunk_elems,
+                              const SnapBuffers& b, int grid, double* sums_out, gac_result* dev_result,
+                              gac_result* host_result, DecideParams p, int mode, int64_t snap_delta,
+                              hipStream_t stream);
 
 // The finalize step alone, on sums that come from elsewhere (device, 3 doubles): decides and
 // writes the result record like the folded form.

@@ -63,8 +63,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // flight; more resident waves only add contention at the memory controllers.
 // Pass 1 is a pure read stream: one 256-thread workgroup per CU, 8 x 16 B loads per array
 // in flight per lane, non-temporal loads (7.0-7.2 TB/s; 6.7 with six workgroups per CU; 16 or
-// 32 loads per array in flight are 1-2 % slower).  Its snapshot form also stores: there 16
-// loads per array in flight (GAC_SNAP_DEPTH = 2 groups) are 4-7 % faster than 8.
+// 32 loads per array in flight are 1-2 % slower).
 // Pass 2 reads and writes the same lines: 512-thread workgroups that load a whole 64 KiB
 // chunk of each array and then store it (8 vectors per lane), on 13/16 of the CUs (3/4 to
 // 7/8 measure within 1 %, all CUs 1.3 % slower, 5/8 4 % slower), non-temporal loads and
@@ -78,21 +77,6 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #endif
 #ifndef GAC_REDUCE_NT_LOAD
 #define GAC_REDUCE_NT_LOAD 1
-#endif
-#ifndef GAC_SNAP_THREADS
-#define GAC_SNAP_THREADS GAC_REDUCE_THREADS
-#endif
-#ifndef GAC_SNAP_UNROLL
-#define GAC_SNAP_UNROLL GAC_REDUCE_UNROLL
-#endif
-#ifndef GAC_SNAP_DEPTH
-#define GAC_SNAP_DEPTH 2
-#endif
-#ifndef GAC_REDUCE_DEPTH
-#define GAC_REDUCE_DEPTH 1
-#endif
-#ifndef GAC_SNAP_NT_STORE
-#define GAC_SNAP_NT_STORE 1
 #endif
 #ifndef GAC_APPLY_THREADS
 #define GAC_APPLY_THREADS 512
@@ -236,6 +220,20 @@ __device__ __forceinline__ Chunk locate(const Seg* __restrict__ segs, int& t, in
   ch.tensor = t;
   return ch;
 }
+
+// A value that is the same in every lane (read from LDS, say), moved to scalar registers so
+// that what depends on it (table lookups, loop control) is scalar work.
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(static_cast<uint64_t>(v) >> 32));
+  return static_cast<int64_t>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
+// One chunk of g and of d in registers: U vectors per lane and array.
+template <int U>
+struct PairTile {
+  u32x4 a[U], b[U];
+};
 
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
@@ -430,22 +428,18 @@ struct SnapArgs {
 // that all partial sums have been written, adds them in the fixed order and does what follows
 // the sums (FinalArgs), so the step needs no separate finalize launch.  It also puts the
 // ticket counter back to zero for the next launch.
-template <int DT, int T, int U, int LD, bool SNAP>
+//
+// The chunk -> workgroup map is a static stride on purpose: for this pure read stream it
+// measured 10 % FASTER than chunks drawn in order (4.24 ms against 4.75-4.94 ms on the
+// 7.6B-parameter bf16 list), the opposite of the passes that also write.
+template <int DT, int T, int U>
 __global__ __launch_bounds__(T) void reduce_kernel(const Seg* __restrict__ segs,
                                                           int64_t n_chunks, int chunk_elems,
                                                           double* __restrict__ partials,
                                                           unsigned int* __restrict__ ticket,
-                                                          FinalArgs fin, SnapArgs snap) {
+                                                          FinalArgs fin) {
   constexpr int N = Elem<DT>::kPerVec;
   const int tid = threadIdx.x;
-  int64_t d_off = 0, spare_off = 0;  // byte offsets from Seg::b of the state read / the buffer written
-  if constexpr (SNAP) {
-    if (*snap.cur) {
-      d_off = snap.delta;
-    } else {
-      spare_off = snap.delta;
-    }
-  }
   double acc[3] = {0.0, 0.0, 0.0};
   int t = 0;
   int64_t c = blockIdx.x;
@@ -461,58 +455,38 @@ __global__ __launch_bounds__(T) void reduce_kernel(const Seg* __restrict__ segs,
     if (more) next = locate<false>(segs, t, c, chunk_elems, Elem<DT>::kSize);
     {
       const gvec* __restrict__ gv = reinterpret_cast<const gvec*>(ch.a);
-      const gvec* __restrict__ dv = reinterpret_cast<const gvec*>(ch.b + d_off);
-      gvec* __restrict__ sv = reinterpret_cast<gvec*>(ch.b + spare_off);
+      const gvec* __restrict__ dv = reinterpret_cast<const gvec*>(ch.b);
       const int nvec = ch.len / N;
       int i = tid;
-      // One group = U vectors per array and lane: products and their sum in fp32, then one
-      // fp64 accumulation.  LD groups are loaded before any of them is used (more bytes in
-      // flight, which a pass that also stores needs); the arithmetic and its order are those
-      // of LD = 1, so the sums do not depend on LD.
-      auto groups = [&](auto depth) {
-        constexpr int D = decltype(depth)::value;
-        for (; i + (D * U - 1) * T < nvec; i += D * U * T) {
-          u32x4 a[D * U], b[D * U];
+      for (; i + (U - 1) * T < nvec; i += U * T) {
+        u32x4 a[U], b[U];
 #pragma unroll
-          for (int u = 0; u < D * U; ++u) a[u] = ld16<GAC_REDUCE_NT_LOAD>(gv + i + u * T);
+        for (int u = 0; u < U; ++u) a[u] = ld16<GAC_REDUCE_NT_LOAD>(gv + i + u * T);
 #pragma unroll
-          for (int u = 0; u < D * U; ++u) b[u] = ld16<GAC_REDUCE_NT_LOAD>(dv + i + u * T);
-          if constexpr (SNAP) {
+        for (int u = 0; u < U; ++u) b[u] = ld16<GAC_REDUCE_NT_LOAD>(dv + i + u * T);
+        float gd = 0.f, gg = 0.f, dd = 0.f;
 #pragma unroll
-            for (int u = 0; u < D * U; ++u) st16<GAC_SNAP_NT_STORE>(sv + i + u * T, a[u]);
-          }
-#pragma unroll
-          for (int grp = 0; grp < D; ++grp) {
-            float gd = 0.f, gg = 0.f, dd = 0.f;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-              float pgd = 0.f, pgg = 0.f, pdd = 0.f;
-              dot3<DT>(a[grp * U + u], b[grp * U + u], pgd, pgg, pdd);
-              gd += pgd;
-              gg += pgg;
-              dd += pdd;
-            }
-            acc[0] += static_cast<double>(gd);
-            acc[1] += static_cast<double>(gg);
-            acc[2] += static_cast<double>(dd);
-          }
+        for (int u = 0; u < U; ++u) {
+          float pgd = 0.f, pgg = 0.f, pdd = 0.f;
+          dot3<DT>(a[u], b[u], pgd, pgg, pdd);
+          gd += pgd;
+          gg += pgg;
+          dd += pdd;
         }
-      };
-      if constexpr (LD > 1) groups(std::integral_constant<int, LD>{});
-      groups(std::integral_constant<int, 1>{});
+        acc[0] += static_cast<double>(gd);
+        acc[1] += static_cast<double>(gg);
+        acc[2] += static_cast<double>(dd);
+      }
       for (; i < nvec; i += T) {
         float gd = 0.f, gg = 0.f, dd = 0.f;
-        const u32x4 a = ld16<GAC_REDUCE_NT_LOAD>(gv + i);
-        dot3<DT>(a, ld16<GAC_REDUCE_NT_LOAD>(dv + i), gd, gg, dd);
-        if constexpr (SNAP) st16<GAC_SNAP_NT_STORE>(sv + i, a);
+        dot3<DT>(ld16<GAC_REDUCE_NT_LOAD>(gv + i), ld16<GAC_REDUCE_NT_LOAD>(dv + i), gd, gg, dd);
         acc[0] += static_cast<double>(gd);
         acc[1] += static_cast<double>(gg);
         acc[2] += static_cast<double>(dd);
       }
       const int e = nvec * N + tid;  // at most N-1 leftover elements
       if (e < ch.len) {
-        const float x = load_elem<DT>(ch.a, e), y = load_elem<DT>(ch.b + d_off, e);
-        if constexpr (SNAP) copy_elem<DT>(ch.a, ch.b + spare_off, e);
+        const float x = load_elem<DT>(ch.a, e), y = load_elem<DT>(ch.b, e);
         acc[0] += static_cast<double>(x * y);
         acc[1] += static_cast<double>(x * x);
         acc[2] += static_cast<double>(y * y);
@@ -536,6 +510,195 @@ __global__ __launch_bounds__(T) void reduce_kernel(const Seg* __restrict__ segs,
   if (tid == 0) {
     finish(s, fin);
     *ticket = 0u;
+  }
+}
+
+// Pass 1 of the snapshot form: the three sums AND the raw gradient stored into the spare state
+// buffer (2 N s read, N s written).  A pass that also writes is fastest with its chunks drawn
+// in order (see walk_tiles; here 7.9 -> 6.9 ms against the static stride), so the sums cannot
+// be per-workgroup partials: which workgroup takes which chunk is not reproducible.  Instead
+// every CHUNK gets its own partial sums, computed by a tree that depends on nothing but the
+// chunk (per lane two fp32 group sums of 8 vectors each, widened and added; a wave reduction;
+// the four waves in order), and snap_combine_kernel adds them in two fixed levels.  The result
+// therefore does not depend on the grid or on timing, only on the data, the chunk size and
+// this tree.  (Publishing the chunk sums and combining them inside this kernel needs a
+// device-wide fence per chunk, which waits for the chunk's stores to drain: 18.7 ms.)
+struct SnapWork {
+  unsigned long long* draw;   // chunk counter of this pass (zero at launch; the combine kernel zeroes it)
+  double* chunk_sums;         // 3 doubles per chunk
+  double* group_sums;         // 3 doubles per group of kSnapGroup chunks
+  unsigned int* ticket;       // arrival counter of the combine kernel's workgroups (left at zero)
+};
+constexpr int kSnapGroup = 256;
+constexpr int kSnapThreads = 256;  // one wave per SIMD; the whole chunk in registers, twice
+constexpr int kSnapVecs = 16;      // vectors per lane and array of a whole chunk
+
+template <int DT>
+__global__ __launch_bounds__(kSnapThreads) void snap_reduce_kernel(const Seg* __restrict__ segs,
+                                                                   int64_t n_chunks, int chunk_elems,
+                                                                   SnapWork w, SnapArgs snap) {
+  constexpr int N = Elem<DT>::kPerVec;
+  constexpr int T = kSnapThreads, U = kSnapVecs, G = 8;  // G vectors per fp32 group, as in reduce_kernel
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bool second = *snap.cur != 0;
+  const int64_t d_off = second ? snap.delta : 0, spare_off = second ? 0 : snap.delta;
+
+  __shared__ unsigned long long drawn[2];
+  __shared__ double wave_part[2][3][T / 64];
+  typedef PairTile<U> Tile;
+  auto whole = [&](const Chunk& ch) { return ch.len == T * U * N; };
+  auto draw = [&](int slot) {
+    if (tid == 0) drawn[slot] = gridDim.x + atomicAdd(w.draw, 1ull);
+  };
+  auto load_tile = [&](const Chunk& ch, Tile& tl) {
+    const gvec* gv = reinterpret_cast<const gvec*>(ch.a) + tid;
+    const gvec* dv = reinterpret_cast<const gvec*>(ch.b + d_off) + tid;
+#pragma unroll
+    for (int u = 0; u < U; ++u) tl.a[u] = ld16<GAC_REDUCE_NT_LOAD>(gv + u * T);
+#pragma unroll
+    for (int u = 0; u < U; ++u) tl.b[u] = ld16<GAC_REDUCE_NT_LOAD>(dv + u * T);
+  };
+  // per-lane contribution of one chunk (and the snapshot stores)
+  auto whole_chunk = [&](const Chunk& ch, const Tile& tl, double (&v)[3]) {
+    gvec* sv = reinterpret_cast<gvec*>(ch.b + spare_off) + tid;
+#pragma unroll
+    for (int u = 0; u < U; ++u) st16<1>(sv + u * T, tl.a[u]);
+    v[0] = v[1] = v[2] = 0.0;
+#pragma unroll
+    for (int grp = 0; grp < U / G; ++grp) {
+      float gd = 0.f, gg = 0.f, dd = 0.f;
+#pragma unroll
+      for (int u = 0; u < G; ++u) {
+        float pgd = 0.f, pgg = 0.f, pdd = 0.f;
+        dot3<DT>(tl.a[grp * G + u], tl.b[grp * G + u], pgd, pgg, pdd);
+        gd += pgd;
+        gg += pgg;
+        dd += pdd;
+      }
+      v[0] += static_cast<double>(gd);
+      v[1] += static_cast<double>(gg);
+      v[2] += static_cast<double>(dd);
+    }
+  };
+  auto ragged_chunk = [&](const Chunk& ch, double (&v)[3]) {  // a tensor's tail, or another chunk size
+    const gvec* gv = reinterpret_cast<const gvec*>(ch.a);
+    const gvec* dv = reinterpret_cast<const gvec*>(ch.b + d_off);
+    gvec* sv = reinterpret_cast<gvec*>(ch.b + spare_off);
+    v[0] = v[1] = v[2] = 0.0;
+    const int nvec = ch.len / N;
+    for (int i = tid; i < nvec; i += T) {
+      float gd = 0.f, gg = 0.f, dd = 0.f;
+      const u32x4 a = ld16<GAC_REDUCE_NT_LOAD>(gv + i);
+      dot3<DT>(a, ld16<GAC_REDUCE_NT_LOAD>(dv + i), gd, gg, dd);
+      st16<1>(sv + i, a);
+      v[0] += static_cast<double>(gd);
+      v[1] += static_cast<double>(gg);
+      v[2] += static_cast<double>(dd);
+    }
+    const int e = nvec * N + tid;  // at most N-1 leftover elements
+    if (e < ch.len) {
+      const float x = load_elem<DT>(ch.a, e), y = load_elem<DT>(ch.b + d_off, e);
+      copy_elem<DT>(ch.a, ch.b + spare_off, e);
+      v[0] += static_cast<double>(x * y);
+      v[1] += static_cast<double>(x * x);
+      v[2] += static_cast<double>(y * y);
+    }
+  };
+
+  int t = 0;
+  int64_t cr = blockIdx.x;
+  if (cr >= n_chunks) return;
+  draw(0);
+  Chunk cur = locate<false>(segs, t, cr, chunk_elems, Elem<DT>::kSize);
+  bool cur_whole = whole(cur);
+  Tile tc = {};
+  if (cur_whole) load_tile(cur, tc);
+  int slot = 0;  // parity of the iteration: which half of the LDS hand-over buffers is written now
+  for (;;) {
+    // (1) this chunk's per-lane sums and its snapshot stores
+    double v[3];
+    if (cur_whole) {
+      whole_chunk(cur, tc, v);
+    } else {
+      ragged_chunk(cur, v);
+    }
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      v[k] = wave_sum(v[k]);
+      if (lane == 0) wave_part[slot][k][wave] = v[k];
+    }
+    __syncthreads();  // the wave sums and the index drawn one iteration ago are visible
+    const int64_t this_chunk = cr;
+    cr = uniform64(static_cast<int64_t>(drawn[slot]));
+    const bool more = cr < n_chunks;
+    // (2) the next chunk's loads go out before anything else
+    Chunk next = cur;
+    bool next_whole = false;
+    Tile tn = {};
+    if (more) {
+      draw(slot ^ 1);
+      next = locate<false>(segs, t, cr, chunk_elems, Elem<DT>::kSize);
+      next_whole = whole(next);
+      if (next_whole) load_tile(next, tn);
+    }
+    // (3) lane 0 adds the four waves in order and stores this chunk's sums
+    if (tid == 0) {
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        double p = wave_part[slot][k][0];
+#pragma unroll
+        for (int x = 1; x < T / 64; ++x) p += wave_part[slot][k][x];
+        w.chunk_sums[3 * this_chunk + k] = p;
+      }
+    }
+    if (!more) break;
+    cur = next;
+    cur_whole = next_whole;
+    tc = tn;
+    slot ^= 1;
+  }
+}
+
+// The chunk sums of snap_reduce_kernel, added in two fixed levels: workgroup s takes groups s,
+// s + gridDim.x, ... of kSnapGroup consecutive chunks each (lane j the group's chunk j, then
+// the fixed tree of block_sum3); the last workgroup to finish adds the group sums in index
+// order and does the finalize step.  An empty list has no groups and its sums are zero.
+__global__ __launch_bounds__(kThreads) void snap_combine_kernel(int64_t n_chunks, SnapWork w,
+                                                                FinalArgs fin) {
+  static_assert(kSnapGroup == kThreads, "one lane per chunk of a group");
+  const int tid = threadIdx.x;
+  const int64_t n_groups = (n_chunks + kSnapGroup - 1) / kSnapGroup;
+  for (int64_t grp = blockIdx.x; grp < n_groups; grp += gridDim.x) {
+    const int64_t first = grp * kSnapGroup;
+    const int64_t count = n_chunks - first < kSnapGroup ? n_chunks - first : kSnapGroup;
+    double s[3] = {0.0, 0.0, 0.0};
+    if (tid < count) {
+      s[0] = w.chunk_sums[3 * (first + tid) + 0];
+      s[1] = w.chunk_sums[3 * (first + tid) + 1];
+      s[2] = w.chunk_sums[3 * (first + tid) + 2];
+    }
+    block_sum3<kThreads>(s);
+    if (tid == 0) {
+      w.group_sums[3 * grp + 0] = s[0];
+      w.group_sums[3 * grp + 1] = s[1];
+      w.group_sums[3 * grp + 2] = s[2];
+    }
+    __syncthreads();  // block_sum3's LDS is free again
+  }
+  __shared__ int last_arrival;
+  if (tid == 0) {
+    __threadfence();
+    last_arrival = atomicAdd(w.ticket, 1u) == gridDim.x - 1;
+  }
+  __syncthreads();
+  if (!last_arrival) return;
+  __threadfence();
+  double g3[3];
+  combine_partials<kThreads>(w.group_sums, static_cast<int>(n_groups), g3);
+  if (tid == 0) {
+    finish(g3, fin);
+    *w.ticket = 0u;
+    *w.draw = 0ull;
   }
 }
 
@@ -613,12 +776,6 @@ __device__ __forceinline__ void apply_chunk_generic(const Chunk& ch, bool projec
 // streamed the list front to back, so its last chunks would be the ones still cached).  With
 // the non-temporal loads of pass 1 this measured no different from a forward walk on 2-3 GB
 // lists; it is kept because it costs nothing.
-__device__ __forceinline__ int64_t uniform64(int64_t v) {
-  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
-  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(static_cast<uint64_t>(v) >> 32));
-  return static_cast<int64_t>((static_cast<uint64_t>(hi) << 32) | lo);
-}
-
 template <int DT, int T, int U, typename Tile, typename Load, typename Store, typename Generic>
 __device__ __forceinline__ void walk_tiles(const Seg* __restrict__ segs, int n_tensors,
                                            int64_t n_chunks, int chunk_elems,
@@ -667,12 +824,6 @@ __device__ __forceinline__ void walk_tiles(const Seg* __restrict__ segs, int n_t
     tc = tn;
   }
 }
-
-// Two register tiles' worth of one chunk of g and of d.
-template <int U>
-struct PairTile {
-  u32x4 a[U], b[U];
-};
 
 // Pass 2, in place: g <- scale_g g + coef_d d where the step projects and/or clips, d <- raw g.
 //
@@ -1166,26 +1317,38 @@ FinalArgs final_args(const double* sums_in, double* sums_out, gac_result* dev_re
 hipError_t launch_reduce(int dtype, const Seg* dev_segs, int64_t n_chunks, int chunk_elems,
                          double* dev_partials, unsigned int* dev_ticket, int grid, double* sums_out,
                          gac_result* dev_result, gac_result* host_result, DecideParams p, int mode,
-                         int64_t snap_delta, hipStream_t stream) {
+                         hipStream_t stream) {
   // the combine of the folded finalize step must be the one of the stand-alone kernel, bit for bit
   static_assert(GAC_REDUCE_THREADS == kThreads, "the fixed-order combine assumes kThreads lanes");
   const FinalArgs f = final_args(nullptr, sums_out, dev_result, host_result, p, mode | 1);
-  const SnapArgs sn = {p.cur, snap_delta};
   constexpr int T = GAC_REDUCE_THREADS, U = GAC_REDUCE_UNROLL;
-  if (p.cur != nullptr) {
-    constexpr int TS = GAC_SNAP_THREADS, US = GAC_SNAP_UNROLL;
-    if (dtype == GAC_F32) {
-      reduce_kernel<GAC_F32, TS, US, GAC_SNAP_DEPTH, true><<<grid, TS, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
-    } else {
-      reduce_kernel<GAC_BF16, TS, US, GAC_SNAP_DEPTH, true><<<grid, TS, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
-    }
+  if (dtype == GAC_F32) {
+    reduce_kernel<GAC_F32, T, U><<<grid, T, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f);
   } else {
-    if (dtype == GAC_F32) {
-      reduce_kernel<GAC_F32, T, U, GAC_REDUCE_DEPTH, false><<<grid, T, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
-    } else {
-      reduce_kernel<GAC_BF16, T, U, GAC_REDUCE_DEPTH, false><<<grid, T, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f, sn);
-    }
+    reduce_kernel<GAC_BF16, T, U><<<grid, T, 0, stream>>>(dev_segs, n_chunks, chunk_elems, dev_partials, dev_ticket, f);
   }
+  return hipGetLastError();
+}
+
+int64_t snap_group_count(int64_t n_chunks) { return (n_chunks + kSnapGroup - 1) / kSnapGroup; }
+
+hipError_t launch_snap_reduce(int dtype, const Seg* dev_segs, int64_t n_chunks, int chunk_elems,
+                              const SnapBuffers& b, int grid, double* sums_out, gac_result* dev_result,
+                              gac_result* host_result, DecideParams p, int mode, int64_t snap_delta,
+                              hipStream_t stream) {
+  const FinalArgs f = final_args(nullptr, sums_out, dev_result, host_result, p, mode | 1);
+  const SnapArgs sn = {p.cur, snap_delta};
+  const SnapWork w = {b.draw, b.chunk_sums, b.group_sums, b.ticket};
+  if (dtype == GAC_F32) {
+    snap_reduce_kernel<GAC_F32><<<grid, kSnapThreads, 0, stream>>>(dev_segs, n_chunks, chunk_elems, w, sn);
+  } else {
+    snap_reduce_kernel<GAC_BF16><<<grid, kSnapThreads, 0, stream>>>(dev_segs, n_chunks, chunk_elems, w, sn);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int64_t n_groups = snap_group_count(n_chunks);
+  const int combine_grid = static_cast<int>(n_groups < 1 ? 1 : (n_groups > 1024 ? 1024 : n_groups));
+  snap_combine_kernel<<<combine_grid, kThreads, 0, stream>>>(n_chunks, w, f);
   return hipGetLastError();
 }
 

@@ -31,7 +31,10 @@ static hipError_t reached(const char* what) {
 }
 int adamw_blocks_per_cu(int) { return 1; }
 hipError_t launch_reduce(int, const Seg*, int64_t, int, double*, unsigned int*, int, double*, gac_result*,
-                         gac_result*, DecideParams, int, int64_t, hipStream_t) { return reached("reduce"); }
+                         gac_result*, DecideParams, int, hipStream_t) { return reached("reduce"); }
+hipError_t launch_snap_reduce(int, const Seg*, int64_t, int, const SnapBuffers&, int, double*, gac_result*,
+                              gac_result*, DecideParams, int, int64_t, hipStream_t) { return reached("snap_reduce"); }
+int64_t snap_group_count(int64_t n) { return (n + 255) / 256; }
 hipError_t launch_finalize(const double*, double*, gac_result*, gac_result*, DecideParams, hipStream_t) { return reached("finalize"); }
 hipError_t launch_apply(int, const Seg*, int, int64_t, int, const gac_result*, unsigned long long*, int, hipStream_t) { return reached("apply"); }
 hipError_t launch_diag(const double*, const int32_t*, int, int64_t, int64_t, double, gac_diag*, gac_diag*, hipStream_t) { return reached("diag"); }
