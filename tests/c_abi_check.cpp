@@ -3,7 +3,11 @@
 // The GPU test that drives it compares the output with the hand-worked cases in
 // tests/golden/gac_len8_cases.txt (derived from Eq. 1 / Appendix A.1, Section 4.2 and Eq. 4).
 //
-//   c_abi_check <f32|bf16> <eps> <c_low> <c_high> <n> d_1..d_n g_1..g_n
+//   c_abi_check <f32|bf16>[:step|:static|:snapshot] <eps> <c_low> <c_high> <n> d_1..d_n g_1..g_n
+//
+// The suffix picks the entry point: gac_step on a context with caller-owned state (default),
+// gac_step_static (no context, nothing allocated), or gac_step on a snapshot-form context
+// (library-owned state, imported and exported).
 #include <hip/hip_runtime_api.h>
 
 #include <cstdint>
@@ -47,7 +51,9 @@ static float from_bf16(uint16_t h) {
 
 int main(int argc, char** argv) {
   if (argc < 6) return 1;
-  const bool bf16 = std::strcmp(argv[1], "bf16") == 0;
+  const bool bf16 = std::strncmp(argv[1], "bf16", 4) == 0;
+  const char* colon = std::strchr(argv[1], ':');
+  const char* entry = colon ? colon + 1 : "step";
   const double eps = std::atof(argv[2]), c_low = std::atof(argv[3]), c_high = std::atof(argv[4]);
   const int n = std::atoi(argv[5]);
   if (argc != 6 + 2 * n) return 1;
@@ -83,13 +89,32 @@ int main(int argc, char** argv) {
   cfg.numel = &numel;
   void* state_list[1] = {dev_state};
   cfg.state_ptrs = state_list;
-  gac_ctx* ctx = nullptr;
-  CHECK_GAC(gac_init(&ctx, &cfg));
   void* ref_list[1] = {dev_ref};
-  CHECK_GAC(gac_state_import(ctx, ref_list, 0, nullptr));  // the reference direction d
   void* grad_list[1] = {dev_g};
   gac_result r;
-  CHECK_GAC(gac_step(ctx, grad_list, nullptr, &r));
+  gac_ctx* ctx = nullptr;
+  if (std::strcmp(entry, "static") == 0) {
+    // no context: the caller's state buffer holds d, the result record lands in device memory
+    CHECK_HIP(hipMemcpy(dev_state, hd.data(), n * es, hipMemcpyHostToDevice));
+    gac_result* dev_r = nullptr;
+    CHECK_HIP(hipMalloc(reinterpret_cast<void**>(&dev_r), sizeof(gac_result)));
+    CHECK_GAC(gac_step_static(&cfg, grad_list, 1, nullptr, dev_r));
+    CHECK_HIP(hipDeviceSynchronize());
+    CHECK_HIP(hipMemcpy(&r, dev_r, sizeof(r), hipMemcpyDeviceToHost));
+    (void)hipFree(dev_r);
+  } else if (std::strcmp(entry, "snapshot") == 0) {
+    cfg.state_ptrs = nullptr;  // the library owns two state buffers
+    cfg.flags = GAC_FLAG_SNAPSHOT_IN_REDUCE;
+    CHECK_GAC(gac_init(&ctx, &cfg));
+    CHECK_GAC(gac_state_import(ctx, ref_list, 0, nullptr));
+    CHECK_GAC(gac_step(ctx, grad_list, nullptr, &r));
+    void* out_list[1] = {dev_state};
+    CHECK_GAC(gac_state_export(ctx, out_list, nullptr, nullptr));
+  } else {
+    CHECK_GAC(gac_init(&ctx, &cfg));
+    CHECK_GAC(gac_state_import(ctx, ref_list, 0, nullptr));  // the reference direction d
+    CHECK_GAC(gac_step(ctx, grad_list, nullptr, &r));
+  }
   CHECK_HIP(hipDeviceSynchronize());
   std::vector<unsigned char> og(n * es), os(n * es);
   CHECK_HIP(hipMemcpy(og.data(), dev_g, n * es, hipMemcpyDeviceToHost));

@@ -22,10 +22,10 @@ def bf16_round(x):
     return u.astype(np.uint32).view(np.float32).astype(np.float64)
 
 
-def run_case(case, dtype):
+def run_case(case, dtype, entry="step"):
     if not os.path.exists(gac_build.C_CHECK_BIN):
         gac_build.build_c_abi_check()
-    args = [gac_build.C_CHECK_BIN, dtype, repr(case["eps"]), "0.05", "0.3", "8"]
+    args = [gac_build.C_CHECK_BIN, f"{dtype}:{entry}", repr(case["eps"]), "0.05", "0.3", "8"]
     args += [repr(x) for x in case["d"]] + [repr(x) for x in case["g"]]
     r = subprocess.run(args, capture_output=True, text=True, timeout=120)
     assert r.returncode == 0, r.stdout + r.stderr
@@ -36,10 +36,13 @@ def run_case(case, dtype):
     return out
 
 
+@pytest.mark.parametrize("entry", ["step", "static", "snapshot"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("case", load_cases(), ids=lambda c: c["case"])
-def test_plain_c_caller_matches_hand_worked_case(case, dtype):
-    out = run_case(case, dtype)
+def test_plain_c_caller_matches_hand_worked_case(case, dtype, entry):
+    """gac_step, gac_step_static (no context, nothing allocated) and gac_step on a snapshot-form
+    context, each from plain C on the hand-worked cases."""
+    out = run_case(case, dtype, entry)
     assert out["sums"] == case["sums"]                      # small integers: exact
     assert out["c"][0] == pytest.approx(case["c"], abs=1e-12)
     assert int(out["regime"][0]) == REGIME[case["regime"]]
