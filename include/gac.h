@@ -175,7 +175,7 @@ void gac_destroy(gac_ctx* ctx);
  *              (pass 2 may still be running) and fills *host_out; the caller skips its
  *              optimizer step if regime is GAC_SKIP.
  * With host_out == NULL and the same pointers as in the previous call, the call only launches
- * its two kernels (no copy, no host wait, no memset), so it can be captured into a HIP graph and
+ * its kernels (two; three in the snapshot form; no copy, no host wait, no memset), so it can be captured into a HIP graph and
  * replayed: the step counter and the record of c_t live on the device and keep counting.
  * Thresholds and max_grad_norm are launch arguments and are frozen into a captured graph.
  * The state d becomes the raw g in all three regimes.  If a sum is not finite (a

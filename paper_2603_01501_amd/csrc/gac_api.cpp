@@ -81,7 +81,7 @@ struct gac_ctx {
   double max_grad_norm = 0;
   int64_t* dev_step = nullptr;  // the step counter lives on the device (see DecideParams)
 
-  // record of (c_t, regime) per step: a ring on the device, written by the finalize kernel
+  // record of (c_t, regime) per step: a ring on the device, written by the finalize step
   double* hist_c = nullptr;
   int32_t* hist_regime = nullptr;
   int hist_cap = 0;
@@ -299,7 +299,7 @@ StepEvents* next_events(gac_ctx* ctx) {
   return &ctx->prof_pool[ctx->prof_used++];
 }
 
-// The finalize kernel writes the result record into pinned host memory itself; an event
+// The finalize step (the tail of pass 1) writes the result record into pinned host memory itself; an event
 // recorded right after it lets the host learn the regime while the apply kernel still runs.
 int mark_result(gac_ctx* ctx, hipStream_t stream) {
   GAC_HIP(ctx, hipEventRecord(ctx->result_event, stream));

@@ -29,11 +29,11 @@ struct AdamSeg {
 };
 static_assert(sizeof(AdamSeg) == 32, "AdamSeg layout is shared with device code");
 
-// What the finalize kernel needs besides the partial sums.
+// What the finalize step needs besides the sums.
 struct DecideParams {
   double c_low, c_high, eps, beta;
   double max_grad_norm;  // 0 = no clipping
-  int64_t* step;         // device-side step counter, incremented by the finalize kernel, so that
+  int64_t* step;         // device-side step counter, incremented by the finalize step, so that
                          // a captured and replayed launch sequence keeps counting
   double* hist_c;        // ring of recorded cosines, hist_cap entries (or null)
   int32_t* hist_regime;  // ring of recorded regimes

@@ -494,7 +494,7 @@ def test_exchange_form_argument_checks():
 # ------------------------------------------------------------------ HIP graph capture
 
 def test_async_step_replayed_from_a_hip_graph():
-    """The asynchronous step is three kernel launches; captured once and replayed, every
+    """The asynchronous step is two kernel launches; captured once and replayed, every
     replay (with eager work and synchronisations in between) must equal the eager step on
     the same inputs, and the device-side step counter and record must keep counting."""
     dtype = torch.bfloat16
