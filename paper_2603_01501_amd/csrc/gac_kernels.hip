@@ -69,6 +69,10 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // 7/8 measure within 1 %, all CUs 1.3 % slower, 5/8 4 % slower), non-temporal loads and
 // stores; 256 x 16 and 1024 x 4 tiles are within 2 % of 512 x 8.  The cache policy of the
 // stores (plain, nt, sc1, sc0 sc1 and combinations) changes a write stream by under 2 %.
+// The fused AdamW pass moves nine streams: 512-thread workgroups with 8 quads per lane and
+// array in flight (one workgroup per CU by register count) beat 256 threads x 2 quads at seven
+// workgroups per CU by 1.3 % on a 14B list, 2 % at 7.6B and 5-6 % at 1.5B, where all arrays
+// share one region of HBM; 1024 x 4 is in between, 16 quads spill.
 #ifndef GAC_REDUCE_THREADS
 #define GAC_REDUCE_THREADS 256
 #endif
@@ -91,13 +95,13 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #define GAC_APPLY_NT_STORE 1
 #endif
 #ifndef GAC_ADAMW_THREADS
-#define GAC_ADAMW_THREADS 256
+#define GAC_ADAMW_THREADS 512
 #endif
 #ifndef GAC_ADAMW_NT_LOAD
 #define GAC_ADAMW_NT_LOAD 1
 #endif
 #ifndef GAC_ADAMW_QUADS
-#define GAC_ADAMW_QUADS 2
+#define GAC_ADAMW_QUADS 8
 #endif
 
 template <int DT> struct Elem;
