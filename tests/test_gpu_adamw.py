@@ -103,6 +103,18 @@ def test_fused_adamw_ragged_list_small_chunks(dtype):
     run_case(RAGGED, dtype, 0.15, 0.3, hyper, 3, B.PROJECT, with_lowp=True, chunk_elems=2048)
 
 
+# The fused pass takes 512 x 8 quads (16,384 elements) per full iteration, then single quads
+# per lane, then single elements: sizes on both sides of each of those edges.
+TILE_EDGES = [(16384,), (16380,), (16388,), (16384 + 2048 + 3,), (2 * 16384 - 4,), (2 * 16384 + 1,),
+              (32768 + 16384 + 5,), (16384 - 2048 - 1,)]
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32], ids=["bf16", "f32"])
+@pytest.mark.parametrize("rho,c_high,expect", [(0.9, 2.0, B.PROJECT), (0.0, 0.3, B.SAFE), (0.9, 0.3, B.SKIP)])
+def test_fused_adamw_sizes_around_the_tile_edges(dtype, rho, c_high, expect):
+    run_case(TILE_EDGES, dtype, rho, c_high, PAPER, 2, expect, with_lowp=True)
+
+
 def test_safe_regime_is_plain_adamw():
     """With a zero reference the step is safe and the fused call must equal torch's AdamW on
     the raw gradient (a library routine, fp32 here, so only to fp32 accuracy)."""
