@@ -72,11 +72,14 @@ def workload(name):
     return [(W.FLAT_N,)], torch.float32, 1, "flat vector"
 
 
-def recorded_traffic(kernel_src_sha):
+def recorded_traffic(kernel_src_sha, workload_name):
     """HBM bytes per apply-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE,
-    scaled by a copy kernel of known size); null unless the recorded figures belong to the
-    kernel source as it is now."""
-    path = os.path.join(ROOT, "profiles", "apply_kernel_7.6B_bf16_pmc.txt")
+    scaled by a copy kernel of known size) on this workload; null for a workload without a
+    counter summary, and unless the recorded figures belong to the kernel source as it is now."""
+    name = {"7.6B": "apply_kernel_7.6B_bf16_pmc.txt", "0.5B": "apply_kernel_0.5B_fp32_pmc.txt"}.get(workload_name)
+    if name is None:
+        return None
+    path = os.path.join(ROOT, "profiles", name)
     if not os.path.exists(path):
         return None
     vals = {}
@@ -443,7 +446,7 @@ def main():
                    "free_gb_requested": args.free_gb if args.free_gb > 0 else None},
         "roofline": {"bound": "hbm", "kernel": "apply_kernel (projection + state update)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": recorded_traffic(sha),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": recorded_traffic(sha, args.workload),
                      "algorithmic_bytes_per_launch": apply_bytes, "avg_launch_ms": ms_app},
         "kernels": {"reduce_kernel (with the finalize step in its last workgroup)":
                         {"avg_ms": ms_red, "bytes": 2.0 * N * es, "GBps": 2.0 * N * es / (ms_red * 1e-3) / 1e9},

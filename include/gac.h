@@ -102,7 +102,7 @@ typedef struct gac_config {
   int32_t grid_blocks;     /* tuning: workgroups of the reduction launch (= number of partial
                               sums, so it is part of what fixes the result bits); 0 = default
                               (one per CU) */
-  int32_t apply_blocks;    /* tuning: workgroups of the apply launch; 0 = default (13/16 of the CUs) */
+  int32_t apply_blocks;    /* tuning: workgroups of the apply launch; 0 = default (7/8 of the CUs) */
   double max_grad_norm;    /* > 0: the gradient handed to the optimizer (g' when projected, g when
                               safe) is scaled by min(1, max_grad_norm / (its 2-norm + 1e-6)); the
                               norm comes from the three sums, so no extra pass.  0 = no clipping.

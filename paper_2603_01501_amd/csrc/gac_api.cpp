@@ -521,14 +521,14 @@ int init_impl(gac_ctx** out, const gac_config* cfg) {
   };
   // Default grids, from measurements on MI355X: the reduction (static striding, one partial
   // sum per workgroup) does best with one workgroup per CU, the in-place pass (chunks drawn
-  // from a counter) with workgroups on 13/16 of the CUs; more requesters lower the achieved
+  // from a counter) with workgroups on 7/8 of the CUs; more requesters lower the achieved
   // HBM bandwidth.
   const int64_t cus = prop.multiProcessorCount;
   ctx->cus = static_cast<int>(cus);
   ctx->apply_blocks_fixed = cfg->apply_blocks > 0;
   ctx->grid = pick_grid(cfg->grid_blocks, cus);
   ctx->grid_state = pick_grid(0, cus * 4);
-  ctx->grid_apply = pick_grid(cfg->apply_blocks, cus * 13 / 16);
+  ctx->grid_apply = pick_grid(cfg->apply_blocks, cus * 7 / 8);
   ctx->grid_adamw = pick_grid(cfg->apply_blocks, cus * gac::adamw_blocks_per_cu(ctx->dtype));
 
   ctx->state.assign(n, nullptr);
@@ -1201,7 +1201,7 @@ int static_step_impl(const gac_config* cfg, void* const* grad_ptrs, int64_t step
   // the same defaults as gac_init, so that the partial sums (and with them every bit of the
   // result) are those of gac_step
   const int grid = pick_grid(cfg->grid_blocks, cus, gac::kStaticMaxGrid);
-  const int grid_apply = pick_grid(cfg->apply_blocks, cus * 13 / 16, gac::kMaxGridBlocks);
+  const int grid_apply = pick_grid(cfg->apply_blocks, cus * 7 / 8, gac::kMaxGridBlocks);
 
   // The tensor table goes to the device as kernel arguments, a batch at a time; the first
   // batch also clears the ticket counter (an earlier call that was cut short may have left it

@@ -64,11 +64,16 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // Pass 1 is a pure read stream: one 256-thread workgroup per CU, 8 x 16 B loads per array
 // in flight per lane, non-temporal loads (7.0-7.2 TB/s; 6.7 with six workgroups per CU; 16 or
 // 32 loads per array in flight are 1-2 % slower).
-// Pass 2 reads and writes the same lines: 512-thread workgroups that load a whole 64 KiB
-// chunk of each array and then store it (8 vectors per lane), on 13/16 of the CUs (3/4 to
-// 7/8 measure within 1 %, all CUs 1.3 % slower, 5/8 4 % slower), non-temporal loads and
-// stores; 256 x 16 and 1024 x 4 tiles are within 2 % of 512 x 8.  The cache policy of the
-// stores (plain, nt, sc1, sc0 sc1 and combinations) changes a write stream by under 2 %.
+// Pass 2 reads and writes the same lines: 512-thread workgroups that load a whole tile of each
+// array and then store it, the next tile's loads issued before the stores, on 7/8 of the CUs
+// (13/16 is 0.4 % slower, 3/4 1.8 %, all CUs 3.5 %), non-temporal loads and stores.  What the
+// tile size has to hit is the length of one burst of stores of a workgroup, 64 KiB: the state
+// copy and the buffer-exchange and snapshot forms write one array and take a 64 KiB chunk per
+// tile (8 vectors per lane); the in-place projection writes two arrays and takes half a chunk
+// of each (4 vectors per lane and array: 9.51 -> 9.04 ms on a 7.6B bf16 list; a quarter
+// chunk 12.2 ms, and half-chunk tiles for the one-array kernels 7.5 against 6.9 ms).  256 x 16
+// and 1024 x 4 tiles are within 3 % of 512 x 8.  The cache policy of the stores (plain, nt,
+// sc1, sc0 sc1 and combinations) changes a write stream by under 2 %.
 // The fused AdamW pass moves nine streams: 512-thread workgroups with 8 quads per lane and
 // array in flight (one workgroup per CU by register count) beat 256 threads x 2 quads at seven
 // workgroups per CU by 1.3 % on a 14B list, 2 % at 7.6B and 5-6 % at 1.5B, where all arrays
@@ -87,6 +92,9 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #endif
 #ifndef GAC_APPLY_UNROLL
 #define GAC_APPLY_UNROLL 8
+#endif
+#ifndef GAC_APPLY_SPLIT
+#define GAC_APPLY_SPLIT 2
 #endif
 #ifndef GAC_APPLY_NT_LOAD
 #define GAC_APPLY_NT_LOAD 1
@@ -236,6 +244,7 @@ __device__ __forceinline__ int64_t uniform64(int64_t v) {
 // One chunk of g and of d in registers: U vectors per lane and array.
 template <int U>
 struct PairTile {
+  static constexpr int kU = U;
   u32x4 a[U], b[U];
 };
 
@@ -759,16 +768,17 @@ __device__ __forceinline__ void apply_chunk_generic(const Chunk& ch, bool projec
   }
 }
 
-// The traversal shared by the pass-2 kernels.  A workgroup of T lanes owns one chunk at a
-// time.  A "whole tile" is an aligned chunk of exactly T*U vectors per array (the default
-// chunk size): each lane then holds U vectors of each array in registers, so the whole chunk
-// is read before any of it is written, and the loads of the workgroup's NEXT whole tile are
-// issued before the current one is computed and stored (two register tiles), which keeps
-// reads in flight during the arithmetic and the stores.  Other chunks (tensor tails,
-// non-default chunk sizes) go to `generic`.
+// The traversal shared by the pass-2 kernels.  A workgroup of T lanes owns one unit of work
+// at a time: a chunk, or one of the SPLIT equal parts of a chunk.  A "whole tile" is a unit of
+// exactly T*U vectors per array (the default chunk size, or its SPLIT-th part): each lane then
+// holds U vectors of each array in registers, so the whole unit is read before any of it is
+// written, and the loads of the workgroup's NEXT whole tile are issued before the current one
+// is computed and stored (two register tiles), which keeps reads in flight during the
+// arithmetic and the stores.  Other units (tensor tails, non-default chunk sizes) go to
+// `generic`.
 //
-// Which workgroup takes which chunk is decided while the kernel runs: workgroup b starts with
-// chunk b and draws every further one from a device-wide counter (*work, zero at launch; the
+// Which workgroup takes which unit is decided while the kernel runs: workgroup b starts with
+// unit b and draws every further one from a device-wide counter (*work, zero at launch; the
 // finalize step resets it).  Pass 2 is element-wise, so the assignment changes no bit of the
 // result, only who is idle at the end: with a static stride the workgroups of half the XCDs
 // finished 0.5-6 % later than the others (measured on MI355X: they see a slower path to
@@ -780,9 +790,9 @@ __device__ __forceinline__ void apply_chunk_generic(const Chunk& ch, bool projec
 // streamed the list front to back, so its last chunks would be the ones still cached).  With
 // the non-temporal loads of pass 1 this measured no different from a forward walk on 2-3 GB
 // lists; it is kept because it costs nothing.
-template <int DT, int T, int U, typename Tile, typename Load, typename Store, typename Generic>
+template <int DT, int T, int U, typename Tile, int SPLIT = 1, typename Load, typename Store, typename Generic>
 __device__ __forceinline__ void walk_tiles(const Seg* __restrict__ segs, int n_tensors,
-                                           int64_t n_chunks, int chunk_elems,
+                                           int64_t n_chunks_whole, int chunk_elems,
                                            unsigned long long* __restrict__ work, Load load_tile,
                                            Store store_tile, Generic generic) {
   constexpr int N = Elem<DT>::kPerVec;
@@ -792,11 +802,27 @@ __device__ __forceinline__ void walk_tiles(const Seg* __restrict__ segs, int n_t
   auto draw = [&](int slot) {
     if (threadIdx.x == 0) drawn[slot] = gridDim.x + atomicAdd(work, 1ull);
   };
+  // The unit of work is 1/SPLIT of a chunk (SPLIT = 1: the chunk itself); units are numbered
+  // like the chunks, the parts of one chunk one after the other.
+  const int64_t n_chunks = n_chunks_whole * SPLIT;
+  const int part = chunk_elems / SPLIT;  // chunk_elems is a multiple of 2048 elements
+  auto locate_unit = [&](int& cursor, int64_t unit) {
+    Chunk ch = locate<true>(segs, cursor, unit / SPLIT, chunk_elems, Elem<DT>::kSize);
+    if constexpr (SPLIT > 1) {
+      const int off = static_cast<int>(unit % SPLIT) * part;
+      const int rest = ch.len - off;
+      ch.len = rest < 0 ? 0 : (rest < part ? rest : part);  // a short chunk leaves late parts empty
+      ch.a += static_cast<int64_t>(off) * Elem<DT>::kSize;
+      ch.b += static_cast<int64_t>(off) * Elem<DT>::kSize;
+      ch.elem_off += off;
+    }
+    return ch;
+  };
   int t = n_tensors - 1;
   int64_t cr = blockIdx.x;
   if (cr >= n_chunks) return;
   draw(0);
-  Chunk cur = locate<true>(segs, t, n_chunks - 1 - cr, chunk_elems, Elem<DT>::kSize);
+  Chunk cur = locate_unit(t, n_chunks - 1 - cr);
   bool cur_whole = whole(cur);
   Tile tc = {};
   if (cur_whole) load_tile(cur, tc);
@@ -810,7 +836,7 @@ __device__ __forceinline__ void walk_tiles(const Seg* __restrict__ segs, int n_t
     Tile tn = {};
     if (more) {
       draw(slot);  // the index after this one: its latency hides behind this tile's traffic
-      next = locate<true>(segs, t, n_chunks - 1 - cr, chunk_elems, Elem<DT>::kSize);
+      next = locate_unit(t, n_chunks - 1 - cr);
       next_whole = whole(next);
       if (next_whole) load_tile(next, tn);
     }
@@ -848,35 +874,49 @@ __global__ __launch_bounds__(T) void apply_kernel(const Seg* __restrict__ segs,
   const float beta = PROBE ? probe_beta : static_cast<float>(res->scale_g);
   const int tid = threadIdx.x;
 
-  typedef PairTile<U> Tile;
-  auto load_tile = [&](const Chunk& ch, Tile& tl) {
-    const gvec* gv = reinterpret_cast<const gvec*>(ch.a) + tid;
-    const gvec* dv = reinterpret_cast<const gvec*>(ch.b) + tid;
+  auto generic = [&](const Chunk& ch) { apply_chunk_generic<DT, T, U, PROBE>(ch, project, k, beta); };
+  if (project) {
+    // Two arrays are read and two written: the tile is a part of a chunk, so that one burst of
+    // stores of a workgroup is as long as in the copy below (tile shapes: see the tuning notes).
+    constexpr int S = GAC_APPLY_SPLIT, UP = U / S;
+    static_assert(U % S == 0 && UP >= 1, "the projecting tile is a whole fraction of the chunk tile");
+    typedef PairTile<UP> Tile;
+    auto load_tile = [&](const Chunk& ch, Tile& tl) {
+      const gvec* gv = reinterpret_cast<const gvec*>(ch.a) + tid;
+      const gvec* dv = reinterpret_cast<const gvec*>(ch.b) + tid;
 #pragma unroll
-    for (int u = 0; u < U; ++u) tl.a[u] = ld16<GAC_APPLY_NT_LOAD>(gv + u * T);
-    if (project) {
+      for (int u = 0; u < UP; ++u) tl.a[u] = ld16<GAC_APPLY_NT_LOAD>(gv + u * T);
 #pragma unroll
-      for (int u = 0; u < U; ++u) tl.b[u] = ld16<GAC_APPLY_NT_LOAD>(dv + u * T);
-    }
-  };
-  auto store_tile = [&](const Chunk& ch, const Tile& tl) {
-    gvec* gv = reinterpret_cast<gvec*>(const_cast<gchar*>(ch.a)) + tid;
-    gvec* dv = reinterpret_cast<gvec*>(ch.b) + tid;
-    if (project) {
+      for (int u = 0; u < UP; ++u) tl.b[u] = ld16<GAC_APPLY_NT_LOAD>(dv + u * T);
+    };
+    auto store_tile = [&](const Chunk& ch, const Tile& tl) {
+      gvec* gv = reinterpret_cast<gvec*>(const_cast<gchar*>(ch.a)) + tid;
+      gvec* dv = reinterpret_cast<gvec*>(ch.b) + tid;
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
+      for (int u = 0; u < UP; ++u) {
         const u32x4 r = project_vec<DT>(tl.a[u], tl.b[u], k, beta);
         st16<GAC_APPLY_NT_STORE>(gv + u * T, PROBE ? same_or(r, tl.a[u]) : r);
         st16<GAC_APPLY_NT_STORE>(dv + u * T, PROBE ? tl.b[u] : tl.a[u]);
       }
-    } else {
+    };
+    walk_tiles<DT, T, UP, Tile, S>(segs, n_tensors, n_chunks, chunk_elems, work, load_tile, store_tile, generic);
+  } else {
+    // state copy only: d <- g, one array each way, whole chunks
+    struct Tile {
+      u32x4 a[U];
+    };
+    auto load_tile = [&](const Chunk& ch, Tile& tl) {
+      const gvec* gv = reinterpret_cast<const gvec*>(ch.a) + tid;
+#pragma unroll
+      for (int u = 0; u < U; ++u) tl.a[u] = ld16<GAC_APPLY_NT_LOAD>(gv + u * T);
+    };
+    auto store_tile = [&](const Chunk& ch, const Tile& tl) {
+      gvec* dv = reinterpret_cast<gvec*>(ch.b) + tid;
 #pragma unroll
       for (int u = 0; u < U; ++u) st16<GAC_APPLY_NT_STORE>(dv + u * T, tl.a[u]);
-    }
-  };
-
-  walk_tiles<DT, T, U, Tile>(segs, n_tensors, n_chunks, chunk_elems, work, load_tile, store_tile,
-                             [&](const Chunk& ch) { apply_chunk_generic<DT, T, U, PROBE>(ch, project, k, beta); });
+    };
+    walk_tiles<DT, T, U, Tile>(segs, n_tensors, n_chunks, chunk_elems, work, load_tile, store_tile, generic);
+  }
 }
 
 // Pass 2 of the buffer-exchange form: the gradient for the optimizer is written over the OLD

@@ -72,6 +72,39 @@ def test_ragged_list_all_regimes(dtype, rho, expect, chunk_elems, grid):
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+@pytest.mark.parametrize("rho,expect", [(0.15, B.PROJECT), (0.0, B.SAFE), (0.9, B.SKIP)])
+@pytest.mark.parametrize("offset", [0, 3])
+def test_sizes_around_the_half_chunk_edges(dtype, rho, expect, offset):
+    """Default chunks.  The projecting pass works on half chunks and the state copy on whole
+    ones: tensors that end just before, at and just after the middle and the end of a chunk,
+    tensors of several chunks, and the same with every tensor starting `offset` elements into
+    its allocation (whole tiles at an address that is only element-aligned)."""
+    chunk = 16384 if dtype == torch.float32 else 32768
+    half = chunk // 2
+    sizes = [half - 1, half, half + 1, half + 9, chunk - 1, chunk, chunk + 1, chunk + half - 7, chunk + half,
+             chunk + half + 8, 3 * chunk - 1, 2 * chunk + half + 1, 1]
+    shapes = [(n,) for n in sizes]
+    g_val, d_val = make(shapes, dtype, rho, config_id=11)
+    g_base = [torch.zeros(n + 8, dtype=dtype, device=DEV) for n in sizes]
+    d_base = [torch.zeros(n + 8, dtype=dtype, device=DEV) for n in sizes]
+    g = [b[offset:offset + n] for b, n in zip(g_base, sizes)]
+    d = [b[(offset + j) % 4:(offset + j) % 4 + n] for j, (b, n) in enumerate(zip(d_base, sizes))]
+    for view, val in zip(g + d, g_val + d_val):
+        view.copy_(val)
+    d_init = U.clone_list(d)
+    ctx = new_ctx(shapes, dtype, state=d)
+    ctx.gac_state_import(d_init, 0)
+    torch.cuda.synchronize()
+    g_pad, d_pad = U.clone_list(g_base), U.clone_list(d_base)
+    step_and_check(ctx, g, d, dtype, expect=expect)
+    # nothing outside the views was written
+    for j, n in enumerate(sizes):
+        o, o2 = offset, (offset + j) % 4
+        assert U.bits_equal(g_base[j][:o], g_pad[j][:o]) and U.bits_equal(g_base[j][o + n:], g_pad[j][o + n:])
+        assert U.bits_equal(d_base[j][:o2], d_pad[j][:o2]) and U.bits_equal(d_base[j][o2 + n:], d_pad[j][o2 + n:])
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
 def test_unaligned_tensors(dtype):
     """Views that start 1..3 elements into an allocation: only element-aligned."""
     sizes = [5000, 40000, 9, 2048]
