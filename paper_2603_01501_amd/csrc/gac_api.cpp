@@ -19,13 +19,12 @@ using gac::Seg;
 namespace {
 
 constexpr int kPinnedSlots = 4;         // ring of pinned staging tables for pointer uploads
-constexpr int kDefaultChunkBytes = 65536;
 constexpr int kChunkMultiple = 2048;    // chunk_elems granularity (256 threads x 8 elements)
 constexpr int kMaxProfiledSteps = 1024;
 
 int64_t elem_size(int dtype) { return dtype == GAC_BF16 ? 2 : 4; }
 
-int default_chunk_elems(int dtype) { return kDefaultChunkBytes / static_cast<int>(elem_size(dtype)); }
+int default_chunk_elems(int dtype) { return gac::kDefaultChunkBytes / static_cast<int>(elem_size(dtype)); }
 
 bool thresholds_ok(double c_low, double c_high) {
   // Section 4.2: 0 < c_low < c_high.  (NaN fails every comparison.)

@@ -9,6 +9,10 @@
 
 namespace gac {
 
+// Default size of a chunk, in bytes of one array.  The pass-2 kernels keep whole tiles of this
+// size (or a fixed fraction of it) in registers; other chunk sizes take their slower generic path.
+constexpr int kDefaultChunkBytes = 65536;
+
 // One entry per tensor plus a sentinel entry (first_chunk = total number of chunks).
 // The tensor list is cut into chunks of at most chunk_elems elements; a chunk never
 // straddles two tensors, so every chunk is one contiguous range of one g and one d.

@@ -63,7 +63,8 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // flight; more resident waves only add contention at the memory controllers.
 // Pass 1 is a pure read stream: one 256-thread workgroup per CU, 8 x 16 B loads per array
 // in flight per lane, non-temporal loads (7.0-7.2 TB/s; 6.7 with six workgroups per CU; 16 or
-// 32 loads per array in flight are 1-2 % slower).
+// 32 loads per array in flight are 1-2 % slower, and so is an explicit second register tile
+// that loads ahead, which is what the passes that also write need).
 // Pass 2 reads and writes the same lines: 512-thread workgroups that load a whole tile of each
 // array and then store it, the next tile's loads issued before the stores, on 7/8 of the CUs
 // (13/16 is 0.4 % slower, 3/4 1.8 %, all CUs 3.5 %), non-temporal loads and stores.  What the
@@ -74,10 +75,10 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // chunk 12.2 ms, and half-chunk tiles for the one-array kernels 7.5 against 6.9 ms).  256 x 16
 // and 1024 x 4 tiles are within 3 % of 512 x 8.  The cache policy of the stores (plain, nt,
 // sc1, sc0 sc1 and combinations) changes a write stream by under 2 %.
-// The fused AdamW pass moves nine streams: 512-thread workgroups with 8 quads per lane and
-// array in flight (one workgroup per CU by register count) beat 256 threads x 2 quads at seven
-// workgroups per CU by 1.3 % on a 14B list, 2 % at 7.6B and 5-6 % at 1.5B, where all arrays
-// share one region of HBM; 1024 x 4 is in between, 16 quads spill.
+// The fused AdamW pass moves nine streams: 512-thread workgroups, one per CU (by register
+// count), two register tiles of 4 quads per lane and array, the next one loading while the
+// current one is stored: 35.4 ms on a 7.6B list against 37.7 ms for one tile of 8 quads
+// (14B: 67.8 against 69.4 ms); two tiles of 2 quads 36.9 ms, 256-thread workgroups 35.9 ms.
 #ifndef GAC_REDUCE_THREADS
 #define GAC_REDUCE_THREADS 256
 #endif
@@ -109,7 +110,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #define GAC_ADAMW_NT_LOAD 1
 #endif
 #ifndef GAC_ADAMW_QUADS
-#define GAC_ADAMW_QUADS 8
+#define GAC_ADAMW_QUADS 4
 #endif
 
 template <int DT> struct Elem;
@@ -1069,113 +1070,163 @@ __device__ __forceinline__ typename Quad<DT>::type pack_quad(const float (&x)[4]
 // The fused pass works in quads (4 elements): lane l of a workgroup takes quads l, l+T, ...
 // so that every load and store instruction of a wave covers one contiguous range, both for
 // the 2-byte gradient / state (8 bytes per lane) and for the 4-byte optimizer state (16 bytes
-// per lane).  Q quads per lane are in flight at a time.
-template <int DT, int Q, int NTL>
-__device__ __forceinline__ void adamw_quads(const gchar* ga, gchar* gb, gfloat* pp, gfloat* pm,
-                                            gfloat* pv, gchar* pl, int j0, int stride,
-                                            bool project, bool skip, float k, float beta,
-                                            const AdamScalars& h) {
-  typedef typename Quad<DT>::type quad_t;
-  typedef GAC_GLOBAL typename Quad<DT>::stored gquad;
-  const gquad* gq = reinterpret_cast<const gquad*>(ga);
-  gquad* dq = reinterpret_cast<gquad*>(gb);
-  gvec* vp = reinterpret_cast<gvec*>(pp);
-  gvec* vm = reinterpret_cast<gvec*>(pm);
-  gvec* vv = reinterpret_cast<gvec*>(pv);
-  gquad* lq = reinterpret_cast<gquad*>(pl);
-  quad_t a[Q];
-#pragma unroll
-  for (int q = 0; q < Q; ++q) {
-    if constexpr (NTL) {
-      a[q] = __builtin_nontemporal_load(gq + j0 + q * stride);
-    } else {
-      a[q] = gq[j0 + q * stride];
-    }
-  }
-  if (skip) {  // violation: only the reference state moves, the optimizer is untouched
-#pragma unroll
-    for (int q = 0; q < Q; ++q) __builtin_nontemporal_store(a[q], dq + j0 + q * stride);
-    return;
-  }
-  quad_t b[Q];
+// per lane).
+
+// The arithmetic of one quad: g' = scale_g g + coef_d d where the step projects and/or clips,
+// then AdamW on p, m, v (updated in place); pnew receives the new parameters.
+template <int DT>
+__device__ __forceinline__ void adamw_quad(typename Quad<DT>::type a, typename Quad<DT>::type b,
+                                           u32x4& P, u32x4& M, u32x4& V, float (&pnew)[4],
+                                           bool project, float k, float beta, const AdamScalars& h) {
+  float x[4];
+  unpack_quad<DT>(a, x);
   if (project) {
+    float y[4];
+    unpack_quad<DT>(b, y);
 #pragma unroll
-    for (int q = 0; q < Q; ++q) {
-      if constexpr (NTL) {
-        b[q] = __builtin_nontemporal_load(dq + j0 + q * stride);
-      } else {
-        b[q] = dq[j0 + q * stride];
-      }
-    }
-  }
-  u32x4 P[Q], M[Q], V[Q];
-#pragma unroll
-  for (int q = 0; q < Q; ++q) {
-    P[q] = ld16<NTL>(vp + j0 + q * stride);
-    M[q] = ld16<NTL>(vm + j0 + q * stride);
-    V[q] = ld16<NTL>(vv + j0 + q * stride);
+    for (int e = 0; e < 4; ++e) x[e] = fmaf(k, y[e], beta * x[e]);
   }
 #pragma unroll
-  for (int q = 0; q < Q; ++q) {
-    float x[4];
-    unpack_quad<DT>(a[q], x);
-    if (project) {
-      float y[4];
-      unpack_quad<DT>(b[q], y);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) x[e] = fmaf(k, y[e], beta * x[e]);
-    }
-    float pnew[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      float p = __uint_as_float(P[q][e]), m = __uint_as_float(M[q][e]), v = __uint_as_float(V[q][e]);
-      adamw_elem(x[e], p, m, v, h);
-      P[q][e] = __float_as_uint(p);
-      M[q][e] = __float_as_uint(m);
-      V[q][e] = __float_as_uint(v);
-      pnew[e] = p;
-    }
-    st16<1>(vp + j0 + q * stride, P[q]);
-    st16<1>(vm + j0 + q * stride, M[q]);
-    st16<1>(vv + j0 + q * stride, V[q]);
-    __builtin_nontemporal_store(a[q], dq + j0 + q * stride);
-    if (pl != nullptr) __builtin_nontemporal_store(pack_quad<DT>(pnew), lq + j0 + q * stride);
+  for (int e = 0; e < 4; ++e) {
+    float p = __uint_as_float(P[e]), m = __uint_as_float(M[e]), v = __uint_as_float(V[e]);
+    adamw_elem(x[e], p, m, v, h);
+    P[e] = __float_as_uint(p);
+    M[e] = __float_as_uint(m);
+    V[e] = __float_as_uint(v);
+    pnew[e] = p;
   }
 }
+
+// One quad from memory to memory (units that are not a whole tile).
+template <int DT, int NTL>
+__device__ __forceinline__ void adamw_single_quad(const gchar* ga, gchar* gb, gfloat* pp, gfloat* pm,
+                                                  gfloat* pv, gchar* pl, int j, bool project,
+                                                  bool skip, float k, float beta,
+                                                  const AdamScalars& h) {
+  typedef typename Quad<DT>::type quad_t;
+  typedef GAC_GLOBAL typename Quad<DT>::stored gquad;
+  const gquad* gq = reinterpret_cast<const gquad*>(ga) + j;
+  gquad* dq = reinterpret_cast<gquad*>(gb) + j;
+  quad_t a, b = {};
+  if constexpr (NTL) {
+    a = __builtin_nontemporal_load(gq);
+  } else {
+    a = *gq;
+  }
+  if (skip) {  // violation: only the reference state moves, the optimizer is untouched
+    __builtin_nontemporal_store(a, dq);
+    return;
+  }
+  if (project) {
+    if constexpr (NTL) {
+      b = __builtin_nontemporal_load(dq);
+    } else {
+      b = *dq;
+    }
+  }
+  gvec* vp = reinterpret_cast<gvec*>(pp) + j;
+  gvec* vm = reinterpret_cast<gvec*>(pm) + j;
+  gvec* vv = reinterpret_cast<gvec*>(pv) + j;
+  u32x4 P = ld16<NTL>(vp), M = ld16<NTL>(vm), V = ld16<NTL>(vv);
+  float pnew[4];
+  adamw_quad<DT>(a, b, P, M, V, pnew, project, k, beta, h);
+  st16<1>(vp, P);
+  st16<1>(vm, M);
+  st16<1>(vv, V);
+  __builtin_nontemporal_store(a, dq);
+  if (pl != nullptr) __builtin_nontemporal_store(pack_quad<DT>(pnew), reinterpret_cast<gquad*>(pl) + j);
+}
+
+// Pass 2 with the optimizer fused in.  The traversal is that of the other pass-2 kernels
+// (walk_tiles): a tile is T x Q quads of each of the five arrays (a quarter of a default bf16
+// chunk, half of an fp32 one), and the next tile's loads are issued before the current tile
+// is computed and stored, so that reads stay in flight while the workgroup stores.
+
+// One tile of the fused pass in registers: Q quads per lane of g, d, p, m and v.
+template <int DT, int Q>
+struct AdamTile {
+  typename Quad<DT>::type a[Q], b[Q];
+  u32x4 P[Q], M[Q], V[Q];
+};
 
 template <int DT, int T>
 __global__ __launch_bounds__(T) void apply_adamw_kernel(
     const Seg* __restrict__ segs, const AdamSeg* __restrict__ adam, int n_tensors,
     int64_t n_chunks, int chunk_elems, const gac_result* __restrict__ res,
     unsigned long long* __restrict__ work, AdamScalars h) {
-  constexpr int Q = GAC_ADAMW_QUADS;
+  constexpr int Q = GAC_ADAMW_QUADS;             // quads per lane and array in one tile
+  constexpr int N = Elem<DT>::kPerVec;
+  constexpr int U = Q * 4 / N;                   // the tile's length in 16-byte vectors of g per lane
+  constexpr int kTileElems = T * Q * 4;
+  constexpr int kChunkElems = kDefaultChunkBytes / Elem<DT>::kSize;
+  constexpr int SPLIT = kChunkElems / kTileElems;  // tiles in a chunk of the default size
+  static_assert(U >= 1 && U * N == Q * 4, "a tile is a whole number of gradient vectors per lane");
+  static_assert(SPLIT >= 1 && SPLIT * kTileElems == kChunkElems, "tiles divide the default chunk");
+  typedef GAC_GLOBAL typename Quad<DT>::stored gquad;
   if (res->nonfinite) return;
-  const int regime = res->regime;
   const bool project = res->modified != 0;  // projected and/or clipped
-  const bool skip = regime == GAC_SKIP;
+  const bool skip = res->regime == GAC_SKIP;
   const float k = static_cast<float>(res->coef_d);
   const float beta = static_cast<float>(res->scale_g);
   const int tid = threadIdx.x;
-  int t = n_tensors - 1;
-  // chunks are drawn from a device-wide counter, one ahead (see walk_tiles)
-  __shared__ unsigned long long drawn[2];
-  int slot = 0;
-  for (int64_t cr = blockIdx.x; cr < n_chunks; slot ^= 1) {
-    if (tid == 0) drawn[slot] = gridDim.x + atomicAdd(work, 1ull);
-    const Chunk ch = locate<true>(segs, t, n_chunks - 1 - cr, chunk_elems, Elem<DT>::kSize);
+
+  typedef AdamTile<DT, Q> Tile;
+  auto load_tile = [&](const Chunk& ch, Tile& tl) {
+    const gquad* gq = reinterpret_cast<const gquad*>(ch.a) + tid;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) tl.a[q] = __builtin_nontemporal_load(gq + q * T);
+    if (skip) return;  // violation: only the reference state moves
+    if (project) {
+      const gquad* dq = reinterpret_cast<const gquad*>(ch.b) + tid;
+#pragma unroll
+      for (int q = 0; q < Q; ++q) tl.b[q] = __builtin_nontemporal_load(dq + q * T);
+    }
+    const AdamSeg as = adam[ch.tensor];
+    const gvec* vp = reinterpret_cast<const gvec*>((const gfloat*)(as.p) + ch.elem_off) + tid;
+    const gvec* vm = reinterpret_cast<const gvec*>((const gfloat*)(as.m) + ch.elem_off) + tid;
+    const gvec* vv = reinterpret_cast<const gvec*>((const gfloat*)(as.v) + ch.elem_off) + tid;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+      tl.P[q] = ld16<GAC_ADAMW_NT_LOAD>(vp + q * T);
+      tl.M[q] = ld16<GAC_ADAMW_NT_LOAD>(vm + q * T);
+      tl.V[q] = ld16<GAC_ADAMW_NT_LOAD>(vv + q * T);
+    }
+  };
+  auto store_tile = [&](const Chunk& ch, const Tile& tl) {
+    gquad* dq = reinterpret_cast<gquad*>(ch.b) + tid;
+    if (skip) {
+#pragma unroll
+      for (int q = 0; q < Q; ++q) __builtin_nontemporal_store(tl.a[q], dq + q * T);
+      return;
+    }
+    const AdamSeg as = adam[ch.tensor];
+    gvec* vp = reinterpret_cast<gvec*>((gfloat*)(as.p) + ch.elem_off) + tid;
+    gvec* vm = reinterpret_cast<gvec*>((gfloat*)(as.m) + ch.elem_off) + tid;
+    gvec* vv = reinterpret_cast<gvec*>((gfloat*)(as.v) + ch.elem_off) + tid;
+    gquad* lq = as.p_lowp ? reinterpret_cast<gquad*>((gchar*)(as.p_lowp) + ch.elem_off * Elem<DT>::kSize) + tid : nullptr;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+      u32x4 P = tl.P[q], M = tl.M[q], V = tl.V[q];
+      float pnew[4];
+      adamw_quad<DT>(tl.a[q], tl.b[q], P, M, V, pnew, project, k, beta, h);
+      st16<1>(vp + q * T, P);
+      st16<1>(vm + q * T, M);
+      st16<1>(vv + q * T, V);
+      __builtin_nontemporal_store(tl.a[q], dq + q * T);
+      if (lq != nullptr) __builtin_nontemporal_store(pack_quad<DT>(pnew), lq + q * T);
+    }
+  };
+  // a unit that is not a whole tile: single quads per lane, then single elements
+  auto generic = [&](const Chunk& ch) {
     const AdamSeg as = adam[ch.tensor];
     gfloat* pp = (gfloat*)(as.p) + ch.elem_off;
     gfloat* pm = (gfloat*)(as.m) + ch.elem_off;
     gfloat* pv = (gfloat*)(as.v) + ch.elem_off;
     gchar* pl = as.p_lowp ? (gchar*)(as.p_lowp) + ch.elem_off * Elem<DT>::kSize : nullptr;
     const int nquad = ch.len / 4;
-    int j = tid;
-    for (; j + (Q - 1) * T < nquad; j += Q * T)
-      adamw_quads<DT, Q, GAC_ADAMW_NT_LOAD>(ch.a, ch.b, pp, pm, pv, pl, j, T, project, skip, k, beta, h);
-    for (; j < nquad; j += T)
-      adamw_quads<DT, 1, GAC_ADAMW_NT_LOAD>(ch.a, ch.b, pp, pm, pv, pl, j, T, project, skip, k, beta, h);
-    const int first_scalar = nquad * 4;
-    for (int i = first_scalar + tid; i < ch.len; i += T) {
+    for (int j = tid; j < nquad; j += T)
+      adamw_single_quad<DT, GAC_ADAMW_NT_LOAD>(ch.a, ch.b, pp, pm, pv, pl, j, project, skip, k, beta, h);
+    for (int i = nquad * 4 + tid; i < ch.len; i += T) {
       if (!skip) {
         float g = load_elem<DT>(ch.a, i);
         if (project) g = fmaf(k, load_elem<DT>(ch.b, i), beta * g);
@@ -1188,11 +1239,9 @@ __global__ __launch_bounds__(T) void apply_adamw_kernel(
       }
       copy_elem<DT>(ch.a, ch.b, i);
     }
-    __syncthreads();
-    cr = uniform64(static_cast<int64_t>(drawn[slot]));
-  }
+  };
+  walk_tiles<DT, T, U, Tile, SPLIT>(segs, n_tensors, n_chunks, chunk_elems, work, load_tile, store_tile, generic);
 }
-
 // ------------------------------------------------------------------ alignment statistics
 
 // Table 3 of the paper: the 0.9-quantile and the maximum of |c_t| and the share of steps

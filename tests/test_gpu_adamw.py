@@ -103,10 +103,12 @@ def test_fused_adamw_ragged_list_small_chunks(dtype):
     run_case(RAGGED, dtype, 0.15, 0.3, hyper, 3, B.PROJECT, with_lowp=True, chunk_elems=2048)
 
 
-# The fused pass takes 512 x 8 quads (16,384 elements) per full iteration, then single quads
+# The fused pass keeps tiles of 512 x 4 quads (8,192 elements: a quarter of a default bf16
+# chunk, half of an fp32 one) in registers and takes what is left of a chunk in single quads
 # per lane, then single elements: sizes on both sides of each of those edges.
-TILE_EDGES = [(16384,), (16380,), (16388,), (16384 + 2048 + 3,), (2 * 16384 - 4,), (2 * 16384 + 1,),
-              (32768 + 16384 + 5,), (16384 - 2048 - 1,)]
+TILE_EDGES = [(8192,), (8188,), (8196,), (8192 + 2048 + 3,), (16384,), (16380,), (16388,), (16384 + 2048 + 3,),
+              (2 * 16384 - 4,), (2 * 16384 + 1,), (3 * 8192 + 5,), (32768 + 16384 + 5,), (16384 - 2048 - 1,),
+              (3 * 32768 + 8192 + 9,)]
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32], ids=["bf16", "f32"])
