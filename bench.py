@@ -76,7 +76,8 @@ def recorded_traffic(kernel_src_sha, workload_name):
     """HBM bytes per apply-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE,
     scaled by a copy kernel of known size) on this workload; null for a workload without a
     counter summary, and unless the recorded figures belong to the kernel source as it is now."""
-    name = {"7.6B": "apply_kernel_7.6B_bf16_pmc.txt", "0.5B": "apply_kernel_0.5B_fp32_pmc.txt"}.get(workload_name)
+    name = {"7.6B": "apply_kernel_7.6B_bf16_pmc.txt", "0.5B": "apply_kernel_0.5B_fp32_pmc.txt",
+            "14B-adamw": "apply_adamw_kernel_14B_bf16_pmc.txt"}.get(workload_name)
     if name is None:
         return None
     path = os.path.join(ROOT, "profiles", name)
@@ -173,6 +174,7 @@ def main_adamw(args):
     import math
     import torch
     from paper_2603_01501_amd import binding as B
+    from paper_2603_01501_amd import build as gac_build
     from paper_2603_01501_amd import workloads as W
     model = {"14B-adamw": W.MODEL_14B, "7.6B-adamw": W.MODEL_76B, "1.5B-adamw": W.MODEL_15B}[args.workload]
     shapes = model.tensor_shapes()
@@ -219,6 +221,15 @@ def main_adamw(args):
             t_adam += 1
     assert res.regime == B.PROJECT, (res.regime, res.c)
     k_red, k_fin, k_app, n = ctx.gac_profile_read()
+    if args.calibration_copy:
+        # one plain copy of known size for a counter profile of this command: the state of a
+        # second, small context (2^30 bf16 elements: 2 GiB read, 2 GiB written) is exported
+        side = B.Gac([1 << 30], B.BF16)
+        dst = [torch.empty(1 << 30, dtype=dtype, device=dev)]
+        side.gac_state_export(dst)
+        torch.cuda.synchronize()
+        side.close()
+        del dst
     ms_step = sum(ms) / len(ms)
     red_bytes, app_bytes = 4.0 * N, 30.0 * N  # bf16 g,d read; + fp32 p,m,v read and written, d written
     out = {"metric": "fused GAC + AdamW step ms and achieved HBM GB/s", "value": (red_bytes + app_bytes) / ms_step / 1e6,
@@ -229,7 +240,8 @@ def main_adamw(args):
                                   "34 bytes per element per step", "cosine": res.c, "t_adam": t_adam},
            "roofline": {"bound": "hbm", "kernel": "apply_adamw_kernel", "achieved": app_bytes / (k_app / n) / 1e6,
                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": app_bytes / (k_app / n) / 1e6 / HBM_PEAK_GBS,
-                        "traffic": None, "algorithmic_bytes_per_launch": app_bytes, "avg_launch_ms": k_app / n},
+                        "traffic": recorded_traffic(gac_build.kernel_code_sha256(), args.workload),
+                        "algorithmic_bytes_per_launch": app_bytes, "avg_launch_ms": k_app / n},
            "kernels": {"reduce_kernel": {"avg_ms": k_red / n, "GBps": red_bytes / (k_red / n) / 1e6},
                        "apply_adamw_kernel": {"avg_ms": k_app / n, "GBps": app_bytes / (k_app / n) / 1e6}}}
     print(json.dumps(out), flush=True)

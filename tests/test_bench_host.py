@@ -25,8 +25,9 @@ def test_traffic_figure_belongs_to_one_kernel_source_and_one_workload():
     sha = build.kernel_code_sha256()
     assert bench.recorded_traffic(sha, "1.5B") is None and bench.recorded_traffic(sha, "flat") is None
     # where a summary exists for the current code, the figure is that workload's own:
-    # 4 N s bytes of the in-place pass within a per cent
-    for name, n, s in (("7.6B", 7615487488, 2), ("0.5B", 494005120, 4)):
+    # 4 N s bytes of the in-place pass (30 N of the fused AdamW pass) within a per cent
+    for name, expected in (("7.6B", 4.0 * 7615487488 * 2), ("0.5B", 4.0 * 494005120 * 4),
+                           ("14B-adamw", 30.0 * 14769689600)):
         t = bench.recorded_traffic(sha, name)
         if t is not None:
-            assert abs(t / (4.0 * n * s) - 1.0) < 0.01, (name, t)
+            assert abs(t / expected - 1.0) < 0.01, (name, t)
