@@ -81,6 +81,56 @@ def test_static_step_equals_context_step_on_calls_in_a_row(dtype):
     assert (rec.c, rec.regime, rec.step) == (0.0, B.SAFE, 9)
 
 
+def test_static_step_replayed_from_a_hip_graph():
+    """gac_step_static only launches kernels, so a caller under stream capture can record it.
+    Captured once (after one eager call, which also settles the library's per-device set-up) and
+    replayed with eager work and synchronisations in between, every replay must equal gac_step
+    on the same inputs; the step number is an argument and therefore the captured one."""
+    dtype = torch.bfloat16
+    shapes = [(70000,), (33,), (0,), (4096,), (9001,)] + [(257 + j,) for j in range(120)]  # two table batches
+    numel = [W.numel(s) for s in shapes]
+    code = U.code(dtype)
+    src = W.AR1Stream(shapes, dtype, 0.2, 1e-3, config_id=43, device=DEV)
+    g = [torch.empty(s, dtype=dtype, device=DEV) for s in shapes]
+    d = [torch.zeros(s, dtype=dtype, device=DEV) for s in shapes]
+    out = torch.zeros(ctypes.sizeof(B.GacResult), dtype=torch.uint8, device=DEV)
+    cfg, keep = B.make_config(numel, code, c_low=0.05, c_high=0.3, eps=EPS, state=d)
+    ref = B.Gac(numel, code, c_low=0.05, c_high=0.3, eps=EPS)
+    src.next_into(g)
+    ref.gac_step(U.clone_list(g))
+    B.gac_step_static(cfg, g, 1, out)       # eager: the first reference is the first gradient
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    src.next_into(g)
+    g_in = U.clone_list(g)
+    with torch.cuda.graph(graph, stream=side):
+        B.gac_step_static(cfg, g, 7, out, stream=torch.cuda.current_stream())
+    regimes = []
+    for i in range(4):
+        if i:
+            src.next_into(g)
+            g_in = U.clone_list(g)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        g_ref = U.clone_list(g_in)
+        want = ref.gac_step(g_ref)
+        torch.cuda.synchronize()
+        got = U.read_device_record(out.data_ptr())
+        assert got.step == 7
+        for name, _ in B.GacResult._fields_:
+            if name != "step":
+                assert getattr(want, name) == getattr(got, name), (i, name)
+        assert all(U.bits_equal(a, b) for a, b in zip(g, g_ref)), f"replay {i}"
+        assert all(U.bits_equal(a, b) for a, b in zip(d, g_in)), f"replay {i}: state"
+        regimes.append(got.regime)
+        _ = sum(float(t.float().sum()) for t in g)  # eager work between replays
+    assert B.PROJECT in regimes
+    ref.close()
+
+
 def test_static_step_rejects_what_does_not_fit():
     n = B.STATIC_MAX_TENSORS + 1
     bufs = [torch.zeros(8, device=DEV) for _ in range(2)]
