@@ -40,8 +40,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=15)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="7.6B",
                     choices=["7.6B", "1.5B", "0.5B", "flat", "14B-adamw", "7.6B-adamw", "1.5B-adamw"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
